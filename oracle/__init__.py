@@ -1,0 +1,96 @@
+"""CPU oracle for sparse graph attention: TEST INFRASTRUCTURE ONLY.
+
+Importable only from tests, the smoke check and the benchmark's cpu_baseline leg.  The
+arithmetic lives in ``sga_oracle.cpp`` (double precision, one function per operator of
+Section 2); this module only marshals numpy arrays.  ``plan_ref`` is the numpy reference of
+the integer scheduling plan.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+from . import plan_ref  # noqa: F401
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsga_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    src = os.path.join(_HERE, "sga_oracle.cpp")
+    if force or not os.path.exists(_LIB_PATH):
+        subprocess.check_call(
+            ["g++", "-O2", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", _LIB_PATH, src]
+        )
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build()
+        lib = ctypes.CDLL(_LIB_PATH)
+        i64, ci, dbl, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+        lib.sga_forward.restype = ci
+        lib.sga_forward.argtypes = [i64, i64, vp, vp, ci, ci, dbl, vp, vp, vp, vp, vp, vp]
+        lib.sga_backward.restype = ci
+        lib.sga_backward.argtypes = [i64, i64, vp, vp, ci, ci, dbl, vp, vp, vp, vp, vp, vp, vp, ci]
+        _lib = lib
+    return _lib
+
+
+def _f64(x):
+    return np.ascontiguousarray(x, dtype=np.float64)
+
+
+def _graph(indptr, indices):
+    return (np.ascontiguousarray(indptr, dtype=np.int64),
+            np.ascontiguousarray(indices, dtype=np.int32))
+
+
+def forward(indptr, indices, Q, K, V, scale=None, want_alpha=False):
+    """Y [n_dst,H,D], lse [n_dst,H] (and U [E,H] when want_alpha) in float64."""
+    lib = _load()
+    indptr, indices = _graph(indptr, indices)
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    n_dst, H, D = Q.shape
+    n_src = K.shape[0]
+    assert indptr.shape[0] == n_dst + 1 and K.shape == V.shape and K.shape[1:] == (H, D)
+    assert indices.shape[0] >= indptr[-1]
+    if indptr[-1] > 0:
+        assert 0 <= indices[:indptr[-1]].min() and indices[:indptr[-1]].max() < n_src
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    Y = np.empty((n_dst, H, D), dtype=np.float64)
+    lse = np.empty((n_dst, H), dtype=np.float64)
+    U = np.empty((int(indptr[-1]), H), dtype=np.float64) if want_alpha else None
+    lib.sga_forward(n_dst, n_src, indptr.ctypes.data, indices.ctypes.data, H, D, float(scale),
+                    Q.ctypes.data, K.ctypes.data, V.ctypes.data, Y.ctypes.data, lse.ctypes.data,
+                    U.ctypes.data if want_alpha else None)
+    return (Y, lse, U) if want_alpha else (Y, lse)
+
+
+def backward(indptr, indices, Q, K, V, dY, scale=None, grouped=True):
+    """dQ [n_dst,H,D], dK, dV [n_src,H,D] in float64 for the loss sum(dY * Y)."""
+    lib = _load()
+    indptr, indices = _graph(indptr, indices)
+    Q, K, V, dY = _f64(Q), _f64(K), _f64(V), _f64(dY)
+    n_dst, H, D = Q.shape
+    n_src = K.shape[0]
+    assert dY.shape == Q.shape and K.shape == V.shape and indptr.shape[0] == n_dst + 1
+    if indptr[-1] > 0:
+        assert 0 <= indices[:indptr[-1]].min() and indices[:indptr[-1]].max() < n_src
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    dQ = np.empty_like(Q)
+    dK = np.empty_like(K)
+    dV = np.empty_like(V)
+    lib.sga_backward(n_dst, n_src, indptr.ctypes.data, indices.ctypes.data, H, D, float(scale),
+                     Q.ctypes.data, K.ctypes.data, V.ctypes.data, dY.ctypes.data,
+                     dQ.ctypes.data, dK.ctypes.data, dV.ctypes.data, int(bool(grouped)))
+    return dQ, dK, dV
