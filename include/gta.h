@@ -1,0 +1,153 @@
+/* gta — sparse graph attention for one MI355X (gfx950): C ABI.
+ *
+ * The library computes the attention core of a sparse graph transformer layer (paper Section
+ * 2.1, Eq. 2, 4, 5; multi-head form as described after Eq. 5) and its gradients (Section 2.2)
+ * for one GPU's share of the graph:
+ *
+ *     s[e,h]   = scale * sum_d Q[i,h,d] * K[j,h,d]        for every stored entry e = (i <- j)   (SDDMM)
+ *     a[e,h]   = exp(s[e,h]) / sum_{e' in row i} exp(s[e',h])                                  (edge softmax)
+ *     out[i,h] = sum_{e in row i} a[e,h] * V[j,h,:]                                            (SpMM)
+ *
+ * The graph is CSR by destination: row i of `indptr`/`indices` lists the sources j that node i
+ * attends to.  Rows are the n_dst nodes owned by this GPU; sources are n_src >= n_dst rows of
+ * K/V (owned nodes first, then halo rows gathered from other GPUs, Algorithm 1).  Every stored
+ * entry is one softmax term (repeated entries count repeatedly, rows need not be sorted).  A row
+ * without entries yields out = 0, lse = -inf and no gradient.
+ *
+ * Pointers.  Unless a parameter says "host", every pointer is a DEVICE pointer owned by the
+ * caller, valid on the current HIP device until the stream work queued by the call has finished.
+ * The library allocates no device memory: plan storage and per-call scratch are caller-provided
+ * (sizes come from the *_bytes queries).  `stream` is a hipStream_t passed as void* (NULL = the
+ * default stream).  gta_attn_fwd / gta_attn_bwd only enqueue work; gta_plan_create synchronises
+ * the stream before returning.
+ *
+ * Layout.  Q, out, dOut, dQ: [n_dst, heads, head_dim]; K, V, dK, dV: [n_src, heads, head_dim];
+ * row-major, contiguous, base 16-byte aligned; elements float (GTA_F32) or bfloat16 (GTA_BF16).
+ * lse: float [n_dst, heads], natural-log sum of exp of the scaled scores.  Accumulation is
+ * always fp32; bf16 outputs are rounded to nearest even.
+ *
+ * Supported shapes: head_dim * sizeof(element) in {32, 64, 128, 256} bytes and
+ * heads * head_dim * sizeof(element) in {128, 256, 512, 1024} bytes; n_dst, n_src, nnz < 2^31.
+ *
+ * Errors.  Every call returns a gta_status and never aborts; on error no output is defined.
+ * gta_last_error() gives a thread-local message for the last failing call of this thread.
+ */
+#ifndef GTA_H_
+#define GTA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GTA_OK = 0,
+    GTA_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned base, inconsistent sizes */
+    GTA_ERR_UNSUPPORTED = 2, /* shape or dtype outside the supported set                        */
+    GTA_ERR_WORKSPACE = 3,   /* workspace / scratch buffer too small                            */
+    GTA_ERR_HIP = 4,         /* a HIP runtime call failed (message in gta_last_error)           */
+    GTA_ERR_GRAPH = 5        /* validate=1 found a malformed CSR                                */
+} gta_status;
+
+typedef enum { GTA_F32 = 0, GTA_BF16 = 1 } gta_dtype;
+
+typedef struct gta_plan gta_plan; /* opaque, host-side handle */
+
+/* Scheduling thresholds; 0 selects the default.  wave_max_deg and hub_chunk must be powers of
+ * two with hub_chunk >= wave_max_deg.
+ *   rows with degree <= wave_max_deg  : one wavefront (or a fraction of one) per row
+ *   rows with degree  > wave_max_deg  : cut into chunks of hub_chunk entries, one workgroup per
+ *                                       chunk; rows with more than one chunk are merged afterwards
+ *   pack_max_deg                      : rows up to this degree are packed several to a wavefront
+ *                                       (0 = chosen per shape at launch)
+ *   validate                          : 1 = check indptr / indices at plan creation            */
+typedef struct {
+    int32_t pack_max_deg;
+    int32_t wave_max_deg;
+    int32_t hub_chunk;
+    int32_t validate;
+} gta_plan_opts;
+
+#define GTA_NUM_CLASSES 33 /* degree classes: 0 for degree 0, else 1 + ceil(log2(degree)) */
+
+typedef struct {
+    int64_t n_dst, n_src, nnz;
+    int32_t pack_max_deg, wave_max_deg, hub_chunk;
+    /* per side (0 = destination rows / in-degree, 1 = source rows / out-degree):              */
+    int64_t n_chunked[2]; /* rows with degree > wave_max_deg (a prefix of bin_rows)             */
+    int64_t n_hub[2];     /* rows with degree > hub_chunk    (a prefix of bin_rows)             */
+    int64_t n_chunks[2];  /* entries of the chunk table                                         */
+} gta_plan_info;
+
+/* Bytes of device workspace gta_plan_create needs for a graph of this size (0 on bad args). */
+size_t gta_plan_workspace_bytes(int64_t n_dst, int64_t n_src, int64_t nnz, const gta_plan_opts* opts);
+
+/* Builds the scheduling plan (integer-only; once per graph).  It consists of
+ *   - per side, row ids ordered by (degree class descending, row id ascending) with class
+ *     offsets, and the chunk table of the rows above wave_max_deg;
+ *   - the transposed pattern t_indptr / t_indices / t_eid ordered by (source ascending, stored
+ *     position ascending), which fixes the summation order of dK and dV (Section 2.2: dK and dV
+ *     are SpMMs with the transposed adjacency).
+ * `workspace` must stay allocated, and indptr / indices unchanged, while the plan is in use.
+ * *plan is a host object released with gta_plan_destroy (which does not touch the workspace). */
+gta_status gta_plan_create(gta_plan** plan, const int64_t* indptr, const int32_t* indices,
+                           int64_t n_dst, int64_t n_src, int64_t nnz, const gta_plan_opts* opts,
+                           void* workspace, size_t workspace_bytes, void* stream);
+void gta_plan_destroy(gta_plan* plan);
+
+gta_status gta_plan_get_info(const gta_plan* plan, gta_plan_info* info /* host */);
+
+/* Copies plan arrays to HOST buffers (any may be NULL to skip); synchronises the device.
+ * side 0: destination rows, side 1: source rows.
+ *   bin_rows  int32 [n_rows]           bin_off   int64 [GTA_NUM_CLASSES + 1]
+ *   chunk_ptr int32 [n_chunked + 1]    chunks    int32 [n_chunks][4] = (row, begin, end, chunks of row) */
+gta_status gta_plan_export_bins(const gta_plan* plan, int side, int32_t* bin_rows, int64_t* bin_off,
+                                int32_t* chunk_ptr, int32_t* chunks);
+/* t_indptr int64 [n_src + 1], t_indices int32 [nnz] (destination of each transposed entry),
+ * t_eid int32 [nnz] (its position in `indices`); HOST buffers, any may be NULL. */
+gta_status gta_plan_export_transpose(const gta_plan* plan, int64_t* t_indptr, int32_t* t_indices,
+                                     int32_t* t_eid);
+
+/* Bytes of device scratch gta_attn_fwd / gta_attn_bwd need (partial results of split rows and
+ * the per-row statistics of the backward pass).  0 on bad args. */
+size_t gta_attn_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
+
+/* Forward (Eq. 4-5 fused: SDDMM -> edge softmax -> SpMM, scores never stored).
+ * scale <= 0 selects 1/sqrt(head_dim).  Writes every row of out and lse. */
+gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                        const void* Q, const void* K, const void* V, void* out, float* lse,
+                        int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
+                        float scale, void* scratch, size_t scratch_bytes, void* stream);
+
+/* Backward (Section 2.2: dV = U^T dY, dU = SDDMM(A, dY, V^T), softmax backward, dQ = dZ K,
+ * dK = dZ^T Q), with the weights recomputed from lse instead of stored.  out and lse are the
+ * forward results.  Writes every row of dQ, dK and dV (dK/dV for all n_src rows, zero where a
+ * source has no entry).  Bitwise reproducible: no floating-point atomics, fixed summation order. */
+gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                        const void* Q, const void* K, const void* V, const void* out,
+                        const float* lse, const void* dOut, void* dQ, void* dK, void* dV,
+                        int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
+                        float scale, void* scratch, size_t scratch_bytes, void* stream);
+
+/* Per-launch timing for benchmarks.  While enabled, every kernel launch of gta_attn_fwd/bwd is
+ * bracketed by HIP events on the call's stream.  gta_profile_read synchronises those events and
+ * copies up to `cap` records to HOST memory (oldest first), returns how many launches were
+ * recorded since the last reset, and clears the list when reset != 0. */
+typedef struct {
+    char name[40];   /* kernel family, e.g. "fwd.wave" */
+    float ms;        /* elapsed time of this launch     */
+    int64_t rows;    /* rows (or chunks) it processed   */
+    int64_t entries; /* stored entries it processed     */
+} gta_launch_record;
+gta_status gta_profile_enable(int on);
+int gta_profile_read(gta_launch_record* out, int cap, int reset);
+
+const char* gta_last_error(void);
+const char* gta_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GTA_H_ */

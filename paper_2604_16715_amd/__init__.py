@@ -1,0 +1,9 @@
+"""gta — sparse graph attention (forward + backward) for one MI355X.
+
+Thin ctypes binding over ``libgta.so`` (C ABI declared in ``include/gta.h``); every step of the
+path runs in the library's HIP kernels.  PyTorch is used for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    GtaError, Plan, gta_attn_bwd, gta_attn_fwd, gta_attn_scratch_bytes, gta_plan_create,
+    gta_profile_enable, gta_profile_read, gta_version, lib_path, load_library,
+)

@@ -1,0 +1,225 @@
+"""ctypes marshalling for libgta.so: argument packing only, no arithmetic."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+NUM_CLASSES = 33
+GTA_F32, GTA_BF16 = 0, 1
+
+
+class GtaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"gta status {status}: {message}")
+        self.status = status
+
+
+class _PlanOpts(Structure):
+    _fields_ = [("pack_max_deg", c_int32), ("wave_max_deg", c_int32), ("hub_chunk", c_int32),
+                ("validate", c_int32)]
+
+
+class _PlanInfo(Structure):
+    _fields_ = [("n_dst", c_int64), ("n_src", c_int64), ("nnz", c_int64),
+                ("pack_max_deg", c_int32), ("wave_max_deg", c_int32), ("hub_chunk", c_int32),
+                ("n_chunked", c_int64 * 2), ("n_hub", c_int64 * 2), ("n_chunks", c_int64 * 2)]
+
+
+class _LaunchRecord(Structure):
+    _fields_ = [("name", c_char * 40), ("ms", c_float), ("rows", c_int64), ("entries", c_int64)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libgta.so")
+
+
+def load_library():
+    """Loads libgta.so; builds it first only when no built library exists.  Never falls back."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(path)
+    vp = c_void_p
+    lib.gta_plan_workspace_bytes.restype = c_size_t
+    lib.gta_plan_workspace_bytes.argtypes = [c_int64, c_int64, c_int64, POINTER(_PlanOpts)]
+    lib.gta_plan_create.restype = c_int
+    lib.gta_plan_create.argtypes = [POINTER(vp), vp, vp, c_int64, c_int64, c_int64, POINTER(_PlanOpts),
+                                    vp, c_size_t, vp]
+    lib.gta_plan_destroy.restype = None
+    lib.gta_plan_destroy.argtypes = [vp]
+    lib.gta_plan_get_info.restype = c_int
+    lib.gta_plan_get_info.argtypes = [vp, POINTER(_PlanInfo)]
+    lib.gta_plan_export_bins.restype = c_int
+    lib.gta_plan_export_bins.argtypes = [vp, c_int, vp, vp, vp, vp]
+    lib.gta_plan_export_transpose.restype = c_int
+    lib.gta_plan_export_transpose.argtypes = [vp, vp, vp, vp]
+    lib.gta_attn_scratch_bytes.restype = c_size_t
+    lib.gta_attn_scratch_bytes.argtypes = [vp, c_int, c_int, c_int]
+    lib.gta_attn_fwd.restype = c_int
+    lib.gta_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int,
+                                 c_float, vp, c_size_t, vp]
+    lib.gta_attn_bwd.restype = c_int
+    lib.gta_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int,
+                                 c_int, c_int, c_float, vp, c_size_t, vp]
+    lib.gta_profile_enable.restype = c_int
+    lib.gta_profile_enable.argtypes = [c_int]
+    lib.gta_profile_read.restype = c_int
+    lib.gta_profile_read.argtypes = [POINTER(_LaunchRecord), c_int, c_int]
+    lib.gta_last_error.restype = c_char_p
+    lib.gta_version.restype = c_char_p
+    _LIB = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise GtaError(status, load_library().gta_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream():
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GTA_F32
+    if t.dtype == torch.bfloat16:
+        return GTA_BF16
+    raise GtaError(2, f"unsupported tensor dtype {t.dtype}")
+
+
+def gta_version() -> str:
+    return load_library().gta_version().decode()
+
+
+class Plan:
+    """Owns the device workspace of a gta_plan and keeps the graph tensors alive."""
+
+    def __init__(self, handle, workspace, indptr, indices, n_dst, n_src):
+        self.handle, self.workspace = handle, workspace
+        self.indptr, self.indices, self.n_dst, self.n_src = indptr, indices, n_dst, n_src
+        self._scratch = {}
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            load_library().gta_plan_destroy(self.handle)
+            self.handle = None
+
+    @property
+    def nnz(self) -> int:
+        return int(self.info().nnz)
+
+    def info(self) -> _PlanInfo:
+        info = _PlanInfo()
+        _check(load_library().gta_plan_get_info(self.handle, ctypes.byref(info)))
+        return info
+
+    def export_bins(self, side: int) -> dict:
+        info = self.info()
+        n_rows = self.n_dst if side == 0 else self.n_src
+        bin_rows = np.empty(n_rows, dtype=np.int32)
+        bin_off = np.empty(NUM_CLASSES + 1, dtype=np.int64)
+        chunk_ptr = np.empty(info.n_chunked[side] + 1, dtype=np.int32)
+        chunks = np.empty((info.n_chunks[side], 4), dtype=np.int32)
+        _check(load_library().gta_plan_export_bins(self.handle, side, bin_rows.ctypes.data, bin_off.ctypes.data,
+                                                   chunk_ptr.ctypes.data, chunks.ctypes.data))
+        return dict(bin_rows=bin_rows, bin_off=bin_off, chunk_ptr=chunk_ptr, chunks=chunks,
+                    n_chunked=int(info.n_chunked[side]), n_hub=int(info.n_hub[side]))
+
+    def export_transpose(self) -> dict:
+        info = self.info()
+        t_indptr = np.empty(self.n_src + 1, dtype=np.int64)
+        t_indices = np.empty(info.nnz, dtype=np.int32)
+        t_eid = np.empty(info.nnz, dtype=np.int32)
+        _check(load_library().gta_plan_export_transpose(self.handle, t_indptr.ctypes.data,
+                                                        t_indices.ctypes.data, t_eid.ctypes.data))
+        return dict(t_indptr=t_indptr, t_indices=t_indices, t_eid=t_eid)
+
+    def scratch(self, heads: int, head_dim: int, dtype_code: int) -> torch.Tensor:
+        key = (heads, head_dim, dtype_code)
+        if key not in self._scratch:
+            nbytes = gta_attn_scratch_bytes(self, heads, head_dim, dtype_code)
+            if nbytes == 0:
+                raise GtaError(2, "unsupported shape for scratch query")
+            self._scratch[key] = torch.empty(nbytes, dtype=torch.uint8, device=self.indptr.device)
+        return self._scratch[key]
+
+
+def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pack_max_deg=0,
+                    wave_max_deg=0, hub_chunk=0, validate=False) -> Plan:
+    lib = load_library()
+    if indptr.dtype != torch.int64 or indices.dtype != torch.int32:
+        raise GtaError(1, "indptr must be int64 and indices int32")
+    if not (indptr.is_cuda and indices.is_cuda and indptr.is_contiguous() and indices.is_contiguous()):
+        raise GtaError(1, "graph tensors must be contiguous device tensors")
+    n_dst = indptr.numel() - 1
+    nnz = indices.numel()
+    opts = _PlanOpts(pack_max_deg, wave_max_deg, hub_chunk, int(bool(validate)))
+    nbytes = lib.gta_plan_workspace_bytes(n_dst, n_src, nnz, ctypes.byref(opts))
+    if nbytes == 0:
+        raise GtaError(1, "bad sizes or plan options")
+    workspace = torch.empty(nbytes, dtype=torch.uint8, device=indptr.device)
+    handle = c_void_p()
+    _check(lib.gta_plan_create(ctypes.byref(handle), _ptr(indptr), _ptr(indices), n_dst, n_src, nnz,
+                               ctypes.byref(opts), _ptr(workspace), nbytes, _stream()))
+    return Plan(handle, workspace, indptr, indices, n_dst, n_src)
+
+
+def gta_attn_scratch_bytes(plan: Plan, heads: int, head_dim: int, dtype_code: int) -> int:
+    return int(load_library().gta_attn_scratch_bytes(plan.handle, heads, head_dim, dtype_code))
+
+
+def gta_attn_fwd(plan: Plan, Q, K, V, scale: float = 0.0, out=None, lse=None):
+    """out [n_dst,H,D] (dtype of Q) and lse [n_dst,H] float32."""
+    n_dst, heads, head_dim = Q.shape
+    code = _dtype_code(Q)
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((n_dst, heads), dtype=torch.float32, device=Q.device)
+    scratch = plan.scratch(heads, head_dim, code)
+    _check(load_library().gta_attn_fwd(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q), _ptr(K),
+                                       _ptr(V), _ptr(out), _ptr(lse), n_dst, K.shape[0], heads, head_dim,
+                                       code, scale, _ptr(scratch), scratch.numel(), _stream()))
+    return out, lse
+
+
+def gta_attn_bwd(plan: Plan, Q, K, V, out, lse, dOut, scale: float = 0.0, dQ=None, dK=None, dV=None):
+    n_dst, heads, head_dim = Q.shape
+    code = _dtype_code(Q)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    scratch = plan.scratch(heads, head_dim, code)
+    _check(load_library().gta_attn_bwd(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q), _ptr(K),
+                                       _ptr(V), _ptr(out), _ptr(lse), _ptr(dOut), _ptr(dQ), _ptr(dK), _ptr(dV),
+                                       n_dst, K.shape[0], heads, head_dim, code, scale, _ptr(scratch),
+                                       scratch.numel(), _stream()))
+    return dQ, dK, dV
+
+
+def gta_profile_enable(on: bool):
+    _check(load_library().gta_profile_enable(int(bool(on))))
+
+
+def gta_profile_read(reset: bool = True):
+    lib = load_library()
+    n = lib.gta_profile_read(None, 0, 0)
+    buf = (_LaunchRecord * max(n, 1))()
+    lib.gta_profile_read(buf, n, int(bool(reset)))
+    return [dict(name=buf[i].name.decode(), ms=float(buf[i].ms), rows=int(buf[i].rows),
+                 entries=int(buf[i].entries)) for i in range(n)]

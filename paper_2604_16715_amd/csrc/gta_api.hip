@@ -1,0 +1,241 @@
+// C ABI entry points, argument checking, shape / schedule resolution and launch timing.
+#include "gta_internal.h"
+
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+namespace gta {
+
+// ---------------------------------------------------------------- errors
+static thread_local char g_error[512] = "";
+
+gta_status fail(gta_status code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// ---------------------------------------------------------------- launch timing
+namespace {
+struct Record {
+    char name[40];
+    int64_t rows, entries;
+    hipEvent_t a, b;
+};
+std::mutex g_prof_mutex;
+std::vector<Record> g_records;
+bool g_profiling = false;
+}  // namespace
+
+LaunchTimer::LaunchTimer(const char* name, int64_t rows, int64_t entries, hipStream_t st)
+    : slot(-1), stream(st) {
+    if (!g_profiling) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    Record r;
+    memset(&r, 0, sizeof r);
+    strncpy(r.name, name, sizeof r.name - 1);
+    r.rows = rows;
+    r.entries = entries;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+    (void)hipEventRecord(r.a, st);
+    g_records.push_back(r);
+    slot = (int)g_records.size() - 1;
+}
+LaunchTimer::~LaunchTimer() {
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (slot < (int)g_records.size()) (void)hipEventRecord(g_records[(size_t)slot].b, stream);
+}
+
+// ---------------------------------------------------------------- shapes and schedules
+gta_status make_shape(int heads, int head_dim, gta_dtype dtype, Shape* out) {
+    if (dtype != GTA_F32 && dtype != GTA_BF16) return fail(GTA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    if (heads <= 0 || head_dim <= 0) return fail(GTA_ERR_INVALID_ARG, "heads and head_dim must be positive");
+    Shape s;
+    s.heads = heads;
+    s.head_dim = head_dim;
+    s.elem_bytes = dtype == GTA_F32 ? 4 : 2;
+    s.nv = 16 / s.elem_bytes;
+    const int head_bytes = head_dim * s.elem_bytes;
+    s.row_bytes = (int64_t)heads * head_bytes;
+    if (head_bytes != 32 && head_bytes != 64 && head_bytes != 128 && head_bytes != 256)
+        return fail(GTA_ERR_UNSUPPORTED, "head_dim*sizeof(element) = %d bytes; supported: 32, 64, 128, 256", head_bytes);
+    if (s.row_bytes != 128 && s.row_bytes != 256 && s.row_bytes != 512 && s.row_bytes != 1024)
+        return fail(GTA_ERR_UNSUPPORTED, "heads*head_dim*sizeof(element) = %lld bytes; supported: 128, 256, 512, 1024",
+                    (long long)s.row_bytes);
+    s.lanes_per_head = head_bytes / 16;
+    s.lanes_per_row = (int)(s.row_bytes / 16);
+    *out = s;
+    return GTA_OK;
+}
+
+Split make_split(const gta_plan* plan, int side, int lanes_per_row) {
+    const Side& sd = plan->side[side];
+    const int W = 64 / lanes_per_row;
+    Split sp;
+    sp.chunk_rows = sd.n_chunked;
+    int pack = plan->pack_max_deg > 0 ? plan->pack_max_deg : 4 * W;
+    if (pack > plan->wave_max_deg) pack = plan->wave_max_deg;
+    int64_t pack_begin = sd.n_rows;
+    if (W > 1) {
+        int p = 0;
+        while ((2 << p) <= pack) ++p;            // largest power of two <= pack is 2^p
+        const int key = class_key(p + 1);          // rows with degree <= 2^p are the classes <= p + 1
+        pack_begin = sd.bin_off[key];
+    }
+    if (pack_begin < sd.n_chunked) pack_begin = sd.n_chunked;
+    sp.wave_begin = sd.n_chunked;
+    sp.wave_end = pack_begin;
+    sp.pack_begin = pack_begin;
+    sp.pack_end = sd.n_rows;
+    sp.chunk_entries = sp.wave_entries = sp.pack_entries = 0;
+    for (int k = 0; k < GTA_NUM_CLASSES; ++k) {
+        const int64_t at = sd.bin_off[k];   // classes are contiguous, so the start decides the schedule
+        if (sd.bin_off[k + 1] == at) continue;
+        if (at < sd.n_chunked) sp.chunk_entries += sd.class_entries[k];
+        else if (at < pack_begin) sp.wave_entries += sd.class_entries[k];
+        else sp.pack_entries += sd.class_entries[k];
+    }
+    return sp;
+}
+
+namespace {
+
+struct ScratchLayout { size_t rowstat, partial, total; };
+
+ScratchLayout scratch_layout(const gta_plan* plan, const Shape& sh) {
+    ScratchLayout L;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t G = (size_t)sh.lanes_per_row, nv = (size_t)sh.nv;
+    const size_t fwd = (size_t)plan->side[0].n_chunks * G * (nv + 2);
+    const size_t bsrc = (size_t)plan->side[1].n_chunks * G * (2 * nv);
+    L.rowstat = 0;
+    L.partial = up(sizeof(float2) * (size_t)plan->n_dst * (size_t)sh.heads);
+    L.total = L.partial + up(sizeof(float) * (fwd > bsrc ? fwd : bsrc)) + 256;
+    return L;
+}
+
+gta_status check_common(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                        int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
+                        float* scale, void* scratch, size_t scratch_bytes, Shape* sh, ScratchLayout* sl) {
+    if (!plan) return fail(GTA_ERR_INVALID_ARG, "plan is null");
+    if (!indptr || (!indices && plan->nnz > 0)) return fail(GTA_ERR_INVALID_ARG, "null graph pointer");
+    if (indptr != plan->indptr || indices != plan->indices)
+        return fail(GTA_ERR_INVALID_ARG, "indptr/indices differ from the arrays the plan was built for");
+    if (n_dst != plan->n_dst || n_src != plan->n_src)
+        return fail(GTA_ERR_INVALID_ARG, "n_dst/n_src differ from the plan's (%lld, %lld)",
+                    (long long)plan->n_dst, (long long)plan->n_src);
+    gta_status rc = make_shape(heads, head_dim, dtype, sh);
+    if (rc != GTA_OK) return rc;
+    if (!(*scale > 0.f)) *scale = 1.0f / sqrtf((float)head_dim);
+    *sl = scratch_layout(plan, *sh);
+    if (!scratch) return fail(GTA_ERR_INVALID_ARG, "scratch is null");
+    if (((uintptr_t)scratch & 255) != 0) return fail(GTA_ERR_INVALID_ARG, "scratch must be 256-byte aligned");
+    if (scratch_bytes < sl->total)
+        return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, sl->total);
+    return GTA_OK;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+}  // namespace
+}  // namespace gta
+
+using namespace gta;
+
+extern "C" GTA_API size_t gta_attn_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype) {
+    Shape sh;
+    if (!plan || make_shape(heads, head_dim, dtype, &sh) != GTA_OK) return 0;
+    return scratch_layout(plan, sh).total;
+}
+
+extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                   const void* Q, const void* K, const void* V, void* out, float* lse,
+                                   int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                                   gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
+                                   void* stream) {
+    Shape sh;
+    ScratchLayout sl;
+    gta_status rc = check_common(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, &scale,
+                                 scratch, scratch_bytes, &sh, &sl);
+    if (rc != GTA_OK) return rc;
+    if ((n_dst > 0 && (!Q || !out || !lse)) || (n_src > 0 && (!K || !V)))
+        return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(out))
+        return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    if (n_dst == 0) return GTA_OK;
+    AttnArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = plan; a.Q = Q; a.K = K; a.V = V; a.o_out = out; a.lse_out = lse;
+    a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
+    a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
+    return launch_fwd(a);
+}
+
+extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                   const void* Q, const void* K, const void* V, const void* out,
+                                   const float* lse, const void* dOut, void* dQ, void* dK, void* dV,
+                                   int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                                   gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
+                                   void* stream) {
+    Shape sh;
+    ScratchLayout sl;
+    gta_status rc = check_common(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, &scale,
+                                 scratch, scratch_bytes, &sh, &sl);
+    if (rc != GTA_OK) return rc;
+    if ((n_dst > 0 && (!Q || !out || !lse || !dOut || !dQ)) || (n_src > 0 && (!K || !V || !dK || !dV)))
+        return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(out) || misaligned(dOut) ||
+        misaligned(dQ) || misaligned(dK) || misaligned(dV))
+        return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    AttnArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = plan; a.Q = Q; a.K = K; a.V = V; a.out = out; a.dO = dOut; a.lse_in = lse;
+    a.dQ = dQ; a.dK = dK; a.dV = dV;
+    a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
+    a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
+    if (n_dst > 0) {
+        rc = launch_bwd_dst(a);
+        if (rc != GTA_OK) return rc;
+    }
+    if (n_src > 0) rc = launch_bwd_src(a);
+    return rc;
+}
+
+extern "C" GTA_API gta_status gta_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_profiling = on != 0;
+    return GTA_OK;
+}
+
+extern "C" GTA_API int gta_profile_read(gta_launch_record* out, int cap, int reset) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    const int n = (int)g_records.size();
+    for (int i = 0; i < n; ++i) {
+        Record& r = g_records[(size_t)i];
+        (void)hipEventSynchronize(r.b);
+        if (out && i < cap) {
+            memcpy(out[i].name, r.name, sizeof r.name);
+            out[i].ms = 0.f;
+            (void)hipEventElapsedTime(&out[i].ms, r.a, r.b);
+            out[i].rows = r.rows;
+            out[i].entries = r.entries;
+        }
+    }
+    if (reset) {
+        for (Record& r : g_records) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        g_records.clear();
+    }
+    return n;
+}
+
+extern "C" GTA_API const char* gta_last_error(void) { return g_error; }
+extern "C" GTA_API const char* gta_version(void) { return "gta 0.1 (gfx950)"; }

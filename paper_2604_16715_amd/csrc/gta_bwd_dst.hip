@@ -1,0 +1,111 @@
+// Backward, destination-major pass (Section 2.2): for every stored entry of row i the weight is
+// recomputed from the saved log-sum-exp, a = exp(s - lse); then
+//     dU = dY_i . v_j                       (the backward SDDMM)
+//     dZ = a * (dU - delta_i)               (softmax backward, delta_i = sum_e a_e dU_e = dY_i . Y_i)
+//     dQ_i += scale * dZ * k_j              (SpMM dQ = dZ K)
+// It also leaves (lse * log2 e, delta) per (row, head) for the source-major pass.
+#include "gta_kernels.h"
+
+namespace gta {
+namespace {
+
+template <class T, int LH_, int G_>
+struct BwdDstPass {
+    static constexpr int LH = LH_, G = G_, U = UnrollFor<G_>::value;
+    static constexpr int NV = Elt<T>::NV;
+    static constexpr int N = NV;   // f = dQ accumulator (unscaled)
+    struct Params {
+        const char *Q, *K, *V, *out, *dO;
+        char* dQ;
+        const float* lse;
+        float2* rowstat;
+        float* partial;
+        int64_t stride;
+        float qscale, scale;
+        int heads;
+    };
+    float q[NV], go[NV];
+    float lse2, delta;
+    float f[N];
+    uint4 kr[U], vr[U];
+
+    __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool primary) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) { q[i] = 0.f; go[i] = 0.f; f[i] = 0.f; }
+        lse2 = 0.f;
+        delta = 0.f;
+        if (active) {
+            float o[NV];
+            Elt<T>::unpack(load16(p.Q, row, p.stride, lig), q);
+            Elt<T>::unpack(load16(p.dO, row, p.stride, lig), go);
+            Elt<T>::unpack(load16(p.out, row, p.stride, lig), o);
+            float d = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) { d = fmaf(go[i], o[i], d); q[i] *= p.qscale; }
+            lse2 = p.lse[(int64_t)row * p.heads + lig / LH] * kLog2e;
+            delta = d;
+        }
+        delta = head_allreduce<LH>(delta);
+        if (active && primary && lig % LH == 0)
+            p.rowstat[(int64_t)row * p.heads + lig / LH] = make_float2(lse2, delta);
+    }
+    __device__ __forceinline__ void load(const Params& p, int u, int j, bool ok, int lig) {
+        kr[u] = make_uint4(0, 0, 0, 0);
+        vr[u] = make_uint4(0, 0, 0, 0);
+        if (ok) {
+            kr[u] = load16(p.K, j, p.stride, lig);
+            vr[u] = load16(p.V, j, p.stride, lig);
+        }
+    }
+    __device__ __forceinline__ void compute(const bool (&ok)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float k[NV], v[NV];
+            Elt<T>::unpack(kr[u], k);
+            Elt<T>::unpack(vr[u], v);
+            float s = 0.f, da = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) { s = fmaf(q[i], k[i], s); da = fmaf(go[i], v[i], da); }
+            s = head_allreduce<LH>(s);
+            da = head_allreduce<LH>(da);
+            const float a = ok[u] ? fast_exp2(s - lse2) : 0.f;
+            const float dz = a * (da - delta);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) f[i] = fmaf(dz, k[i], f[i]);
+        }
+    }
+    static __device__ __forceinline__ void combine(float (&a)[N], const float (&b)[N]) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) a[i] += b[i];
+    }
+    static __device__ __forceinline__ void finish(const Params& p, int row, int lig, const float (&a)[N]) {
+        float o[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) o[i] = a[i] * p.scale;
+        store16(p.dQ, row, p.stride, lig, Elt<T>::pack(o));
+    }
+};
+
+template <class T> gta_status run(const AttnArgs& a) {
+    const Shape& sh = a.shape;
+#define GTA_CALL(LHc, Gc)                                                                            \
+    {                                                                                                \
+        using P = BwdDstPass<T, LHc, Gc>;                                                            \
+        typename P::Params prm{(const char*)a.Q, (const char*)a.K, (const char*)a.V,                 \
+                               (const char*)a.out, (const char*)a.dO, (char*)a.dQ, a.lse_in,         \
+                               a.rowstat, a.partial, sh.row_bytes, a.scale * kLog2e, a.scale,        \
+                               sh.heads};                                                            \
+        return launch_pass<P>("bwd_dst", prm, a.plan, 0, a.stream);                                  \
+    }
+    GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
+#undef GTA_CALL
+    return GTA_OK;
+}
+
+}  // namespace
+
+gta_status launch_bwd_dst(const AttnArgs& a) {
+    return a.shape.elem_bytes == 4 ? run<float>(a) : run<bf16_tag>(a);
+}
+
+}  // namespace gta

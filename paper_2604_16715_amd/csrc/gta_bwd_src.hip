@@ -1,0 +1,105 @@
+// Backward, source-major pass (Section 2.2): the two SpMMs with the transposed adjacency,
+//     dV_j = sum_{i : j in N(i)} a_ij * dY_i          (dV = U^T dY)
+//     dK_j = sum_{i : j in N(i)} scale * dZ_ij * q_i   (dK = dZ^T Q)
+// walked over the plan's transposed pattern so each source row is owned by one group of lanes
+// and summed in a fixed order (no atomics).  Per entry the weight a_ij and dZ_ij are recomputed
+// from q_i, dY_i and the (lse, delta) pair the destination-major pass left for row i.
+#include "gta_kernels.h"
+
+namespace gta {
+namespace {
+
+template <class T, int LH_, int G_>
+struct BwdSrcPass {
+    static constexpr int LH = LH_, G = G_, U = UnrollFor<G_>::value;
+    static constexpr int NV = Elt<T>::NV;
+    static constexpr int N = 2 * NV;   // f = dK accumulator (unscaled), then dV accumulator
+    struct Params {
+        const char *Q, *dO, *K, *V;
+        char *dK, *dV;
+        const float2* rowstat;
+        float* partial;
+        int64_t stride;
+        float qscale, scale;
+        int heads;
+    };
+    float k2[NV], v[NV];
+    float f[N];
+    uint4 qr[U], gr[U];
+    float2 st[U];
+
+    __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) { k2[i] = 0.f; v[i] = 0.f; f[i] = 0.f; f[NV + i] = 0.f; }
+        if (active) {
+            Elt<T>::unpack(load16(p.K, row, p.stride, lig), k2);
+            Elt<T>::unpack(load16(p.V, row, p.stride, lig), v);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) k2[i] *= p.qscale;
+        }
+    }
+    __device__ __forceinline__ void load(const Params& p, int u, int i, bool ok, int lig) {
+        qr[u] = make_uint4(0, 0, 0, 0);
+        gr[u] = make_uint4(0, 0, 0, 0);
+        st[u] = make_float2(0.f, 0.f);
+        if (ok) {
+            qr[u] = load16(p.Q, i, p.stride, lig);
+            gr[u] = load16(p.dO, i, p.stride, lig);
+            st[u] = p.rowstat[(int64_t)i * p.heads + lig / LH];
+        }
+    }
+    __device__ __forceinline__ void compute(const bool (&ok)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float q[NV], go[NV];
+            Elt<T>::unpack(qr[u], q);
+            Elt<T>::unpack(gr[u], go);
+            float s = 0.f, da = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) { s = fmaf(q[i], k2[i], s); da = fmaf(go[i], v[i], da); }
+            s = head_allreduce<LH>(s);
+            da = head_allreduce<LH>(da);
+            const float a = ok[u] ? fast_exp2(s - st[u].x) : 0.f;
+            const float dz = a * (da - st[u].y);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                f[i] = fmaf(dz, q[i], f[i]);
+                f[NV + i] = fmaf(a, go[i], f[NV + i]);
+            }
+        }
+    }
+    static __device__ __forceinline__ void combine(float (&a)[N], const float (&b)[N]) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) a[i] += b[i];
+    }
+    static __device__ __forceinline__ void finish(const Params& p, int row, int lig, const float (&a)[N]) {
+        float dk[NV], dv[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) { dk[i] = a[i] * p.scale; dv[i] = a[NV + i]; }
+        store16(p.dK, row, p.stride, lig, Elt<T>::pack(dk));
+        store16(p.dV, row, p.stride, lig, Elt<T>::pack(dv));
+    }
+};
+
+template <class T> gta_status run(const AttnArgs& a) {
+    const Shape& sh = a.shape;
+#define GTA_CALL(LHc, Gc)                                                                         \
+    {                                                                                             \
+        using P = BwdSrcPass<T, LHc, Gc>;                                                         \
+        typename P::Params prm{(const char*)a.Q, (const char*)a.dO, (const char*)a.K,             \
+                               (const char*)a.V, (char*)a.dK, (char*)a.dV, a.rowstat, a.partial,  \
+                               sh.row_bytes, a.scale * kLog2e, a.scale, sh.heads};                \
+        return launch_pass<P>("bwd_src", prm, a.plan, 1, a.stream);                               \
+    }
+    GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
+#undef GTA_CALL
+    return GTA_OK;
+}
+
+}  // namespace
+
+gta_status launch_bwd_src(const AttnArgs& a) {
+    return a.shape.elem_bytes == 4 ? run<float>(a) : run<bf16_tag>(a);
+}
+
+}  // namespace gta

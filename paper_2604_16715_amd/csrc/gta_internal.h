@@ -1,0 +1,108 @@
+// Internal declarations shared by the translation units of libgta (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+
+#include "gta.h"
+
+#define GTA_API __attribute__((visibility("default")))
+
+namespace gta {
+
+// One side of the plan: the rows of a CSR pattern (destination rows of A, or source rows of
+// A^T) ordered for scheduling.
+struct Side {
+    int64_t n_rows = 0;
+    const int64_t* ptr = nullptr;   // device: row pointer of this side's pattern
+    const int32_t* idx = nullptr;   // device: column ids (the other side's rows)
+    int32_t* bin_rows = nullptr;    // device [n_rows]
+    int32_t* chunk_ptr = nullptr;   // device [n_chunked + 1]
+    int4* chunks = nullptr;         // device [n_chunks] = (row, begin, end, chunks of row)
+    int64_t bin_off[GTA_NUM_CLASSES + 1] = {0};   // host copy
+    int64_t class_entries[GTA_NUM_CLASSES] = {0}; // host: stored entries per degree class (key order)
+    int64_t n_chunked = 0, n_hub = 0, n_chunks = 0;
+};
+
+}  // namespace gta
+
+struct gta_plan {
+    int64_t n_dst = 0, n_src = 0, nnz = 0;
+    int32_t pack_max_deg = 0, wave_max_deg = 0, hub_chunk = 0;
+    int device = 0;
+    const int64_t* indptr = nullptr;
+    const int32_t* indices = nullptr;
+    int64_t* t_indptr = nullptr;   // device [n_src + 1]
+    int32_t* t_indices = nullptr;  // device [nnz]
+    int32_t* t_eid = nullptr;      // device [nnz]
+    gta::Side side[2];
+};
+
+namespace gta {
+
+// ---- error plumbing -------------------------------------------------------------------
+gta_status fail(gta_status code, const char* fmt, ...);
+#define GTA_HIP_TRY(expr)                                                                     \
+    do {                                                                                      \
+        hipError_t _e = (expr);                                                               \
+        if (_e != hipSuccess)                                                                 \
+            return ::gta::fail(GTA_ERR_HIP, "%s failed: %s (%s:%d)", #expr,                   \
+                               hipGetErrorString(_e), __FILE__, __LINE__);                    \
+    } while (0)
+
+// degree class of a row and the sort key that orders rows hubs-first
+__host__ __device__ inline int degree_class(int64_t deg) {
+    if (deg <= 0) return 0;
+    int bits = 0;
+    for (uint64_t t = (uint64_t)(deg - 1); t; t >>= 1) ++bits;
+    return 1 + bits;
+}
+inline int class_key(int cls) { return (GTA_NUM_CLASSES - 1) - cls; }
+
+// ---- per-launch timing ------------------------------------------------------------------
+struct LaunchTimer {   // RAII: records events around one launch when profiling is on
+    LaunchTimer(const char* name, int64_t rows, int64_t entries, hipStream_t stream);
+    ~LaunchTimer();
+    int slot;
+    hipStream_t stream;
+};
+
+// ---- shape handling ---------------------------------------------------------------------
+struct Shape {
+    int heads, head_dim, elem_bytes;
+    int lanes_per_head;   // LH: 16-byte lanes covering one head
+    int lanes_per_row;    // G : 16-byte lanes covering one row
+    int nv;               // values per lane (4 fp32, 8 bf16)
+    int64_t row_bytes;
+};
+gta_status make_shape(int heads, int head_dim, gta_dtype dtype, Shape* out);
+
+// Which rows go to which schedule, resolved from the plan for a given lanes_per_row.
+struct Split {
+    int64_t chunk_rows;            // bin_rows[0 .. chunk_rows)           -> chunk schedule
+    int64_t wave_begin, wave_end;  // bin_rows[wave_begin .. wave_end)    -> one wavefront per row
+    int64_t pack_begin, pack_end;  // bin_rows[pack_begin .. pack_end)    -> several rows per wavefront
+    int64_t wave_entries, pack_entries, chunk_entries;
+};
+Split make_split(const gta_plan* plan, int side, int lanes_per_row);
+
+// arguments common to the attention launches
+struct AttnArgs {
+    const gta_plan* plan;
+    const void *Q, *K, *V, *out, *dO;
+    void *o_out, *dQ, *dK, *dV;
+    const float* lse_in;
+    float* lse_out;
+    float2* rowstat;     // [n_dst, heads] (lse * log2(e), delta)
+    float* partial;      // scratch for split rows
+    float scale;
+    Shape shape;
+    hipStream_t stream;
+};
+
+gta_status launch_fwd(const AttnArgs& a);
+gta_status launch_bwd_dst(const AttnArgs& a);
+gta_status launch_bwd_src(const AttnArgs& a);
+
+}  // namespace gta

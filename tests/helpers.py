@@ -1,0 +1,96 @@
+"""Shared helpers for the GPU parity tests: upload seeded inputs, run the library through its
+C ABI binding, run the oracle on the same inputs, and measure errors."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import gen
+import oracle
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}   # normwise relative tolerances
+
+
+def to_torch(x: np.ndarray, device="cuda") -> torch.Tensor:
+    """Storage array (float32, or uint16 holding bfloat16 bits) -> device tensor."""
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(x).to(device)
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def rel_errors(got: np.ndarray, ref: np.ndarray):
+    """(max-norm error / max|ref|, 2-norm error / 2-norm ref)."""
+    diff = got - ref
+    den_max = max(float(np.max(np.abs(ref))) if ref.size else 0.0, 1e-300)
+    den_l2 = max(float(np.sqrt(np.sum(ref * ref))) if ref.size else 0.0, 1e-300)
+    if ref.size == 0:
+        return 0.0, 0.0
+    return float(np.max(np.abs(diff))) / den_max, float(np.sqrt(np.sum(diff * diff))) / den_l2
+
+
+def assert_close(name, got, ref, tol):
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
+    emax, el2 = rel_errors(got, ref)
+    assert emax <= tol and el2 <= tol, f"{name}: max-norm rel {emax:.3e}, l2 rel {el2:.3e} > {tol:.1e}"
+    return emax, el2
+
+
+def assert_lse_close(got, ref, tol):
+    empty = np.isinf(ref)
+    assert np.array_equal(np.isneginf(got), empty), "lse: -inf pattern differs"
+    g, r = got[~empty], ref[~empty]
+    assert np.all(np.abs(g - r) <= tol * np.maximum(1.0, np.abs(r))), \
+        f"lse: max abs err {np.max(np.abs(g - r)) if g.size else 0:.3e}"
+
+
+class Problem:
+    """Inputs of one workload in storage precision (host) plus their exact float64 widening."""
+
+    def __init__(self, indptr, indices, n_src, Q, K, V, dO, dtype):
+        self.indptr = np.ascontiguousarray(indptr, dtype=np.int64)
+        self.indices = np.ascontiguousarray(indices, dtype=np.int32)
+        self.n_dst, self.n_src = len(indptr) - 1, n_src
+        self.Q, self.K, self.V, self.dO = Q, K, V, dO
+        self.dtype = dtype
+
+    @classmethod
+    def from_workload(cls, w: "gen.Workload"):
+        return cls(w.indptr, w.indices, w.n_src, w.tensor("Q"), w.tensor("K"), w.tensor("V"),
+                   w.tensor("dO"), w.dtype)
+
+    @classmethod
+    def random(cls, indptr, indices, n_src, heads, head_dim, dtype, seed):
+        n_dst = len(indptr) - 1
+        mk = lambda rows, stream: gen.normal((rows, heads, head_dim), dtype, seed, stream)
+        return cls(indptr, indices, n_src, mk(n_dst, 2), mk(n_src, 3), mk(n_src, 4), mk(n_dst, 5), dtype)
+
+    def f64(self, name):
+        return gen.as_f32(getattr(self, name)).astype(np.float64)
+
+    def oracle_forward(self, scale=None):
+        return oracle.forward(self.indptr, self.indices, self.f64("Q"), self.f64("K"), self.f64("V"), scale)
+
+    def oracle_backward(self, scale=None):
+        return oracle.backward(self.indptr, self.indices, self.f64("Q"), self.f64("K"), self.f64("V"),
+                               self.f64("dO"), scale)
+
+
+def run_gpu(p: Problem, scale=0.0, plan_kwargs=None, backward=True):
+    """Plan + forward (+ backward) through the C ABI.  Returns dict of float64 host arrays + plan."""
+    import paper_2604_16715_amd as gta
+    indptr = torch.from_numpy(p.indptr).cuda()
+    indices = torch.from_numpy(p.indices).cuda()
+    plan = gta.gta_plan_create(indptr, indices, p.n_src, validate=True, **(plan_kwargs or {}))
+    Q, K, V, dO = (to_torch(getattr(p, k)) for k in ("Q", "K", "V", "dO"))
+    out, lse = gta.gta_attn_fwd(plan, Q, K, V, scale)
+    res = dict(plan=plan, out=to_f64(out), lse=to_f64(lse), raw_out=out, raw_lse=lse)
+    if backward:
+        dQ, dK, dV = gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO, scale)
+        res.update(dQ=to_f64(dQ), dK=to_f64(dK), dV=to_f64(dV), raw=(dQ, dK, dV))
+    torch.cuda.synchronize()
+    return res
