@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse graph attention hot path (forward + backward) on one MI355X.
+
+A step is one pass of the whole path — gta_attn_fwd then gta_attn_bwd — over one seeded
+synthetic workload whose inputs are already resident in HBM.  Prints ONE JSON line with the
+whole-job throughput in edges/s, a roofline object for the dominant kernel (algorithmic bytes
+over its HIP-event time) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/), keyed by (workload, kernel); absent = not measured.
+MEASURED_TRAFFIC_BYTES: dict = {
+    # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, scale factors from the copy probe
+    ("large", "bwd_src.wave"): int((24510167 * 2.0 + 1618080 * 1.0) * 1024),
+}
+
+
+def algorithmic_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int) -> int:
+    """Bytes the method must move for `rows` rows holding `entries` stored entries: every entry
+    gathers its rows (no reuse assumed), streams are touched once."""
+    R, H = row_bytes, heads
+    if pass_name == "fwd":       # K,V gathers + index | Q read, out write, lse write, row pointer
+        return entries * (2 * R + 4) + rows * (2 * R + 4 * H + 8)
+    if pass_name == "bwd_dst":   # K,V gathers + index | Q,dO,out read, dQ write, lse read, stats write
+        return entries * (2 * R + 4) + rows * (4 * R + 12 * H + 8)
+    if pass_name == "bwd_src":   # Q,dO gathers + stats + index | K,V read, dK,dV write, row pointer
+        return entries * (2 * R + 8 * H + 4) + rows * (4 * R + 8)
+    raise KeyError(pass_name)
+
+
+def cpu_baseline(w, sample_edges: int) -> dict:
+    """Times the oracle (as it stands) on the first rows of the workload holding about
+    `sample_edges` entries; the sources they reference are renumbered compactly."""
+    import gen
+    import oracle
+    n_rows = int(np.searchsorted(w.indptr, min(sample_edges, w.nnz), side="left"))
+    n_rows = max(1, min(n_rows, w.n_dst))
+    nnz = int(w.indptr[n_rows])
+    indptr = w.indptr[: n_rows + 1].copy()
+    uniq, indices = np.unique(w.indices[:nnz], return_inverse=True)
+    indices = indices.astype(np.int32)
+    f64 = lambda x: gen.as_f32(x).astype(np.float64)
+    Q, dO = f64(w.tensor("Q")[:n_rows]), f64(w.tensor("dO")[:n_rows])
+    K, V = f64(w.tensor("K")[uniq]), f64(w.tensor("V")[uniq])
+    t0 = time.perf_counter()
+    oracle.forward(indptr, indices, Q, K, V)
+    t1 = time.perf_counter()
+    oracle.backward(indptr, indices, Q, K, V, dO)
+    t2 = time.perf_counter()
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
+    return {"value": nnz / (t2 - t0), "unit": "edges/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n_rows} destination rows ({nnz} entries, {len(uniq)} distinct sources, "
+                      f"renumbered) of workload '{w.name}', fp64 forward {t1 - t0:.2f}s + backward {t2 - t1:.2f}s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large", choices=["tiny", "mid", "large", "partition", "skew"])
+    ap.add_argument("--shrink", type=int, default=1, help="divide the workload size (debugging)")
+    ap.add_argument("--cpu-sample-edges", type=int, default=8_000_000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pack-max-deg", type=int, default=0)
+    ap.add_argument("--wave-max-deg", type=int, default=0)
+    ap.add_argument("--hub-chunk", type=int, default=0)
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain elementwise copy kernel (reads and writes this many MiB) "
+                         "so that profiler byte counters can be scaled against a known size")
+    ap.add_argument("--verbose", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no cross-GPU sharding or collectives); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import gen
+    import paper_2604_16715_amd as gta
+
+    def log(*a):
+        if args.verbose:
+            print(*a, file=sys.stderr, flush=True)
+
+    t0 = time.perf_counter()
+    w = gen.workload(args.workload, args.shrink)
+    host = {k: w.tensor(k) for k in ("Q", "K", "V", "dO")}
+    log(f"generated {w.name}: n_dst={w.n_dst} n_src={w.n_src} nnz={w.nnz} in {time.perf_counter() - t0:.1f}s")
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def up(x):
+        if x.dtype == np.uint16:
+            return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(x).to(dev)
+
+    indptr, indices = torch.from_numpy(w.indptr).to(dev), torch.from_numpy(w.indices).to(dev)
+    Q, K, V, dO = (up(host[k]) for k in ("Q", "K", "V", "dO"))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plan = gta.gta_plan_create(indptr, indices, w.n_src, pack_max_deg=args.pack_max_deg,
+                               wave_max_deg=args.wave_max_deg, hub_chunk=args.hub_chunk)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    out = torch.empty_like(Q)
+    lse = torch.empty((w.n_dst, w.heads), dtype=torch.float32, device=dev)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+
+    def step():
+        gta.gta_attn_fwd(plan, Q, K, V, 0.0, out, lse)
+        gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO, 0.0, dQ, dK, dV)
+
+    if args.copy_probe_mib > 0:   # calibration kernel for rocprofv3 --pmc runs (outside the timed region)
+        src = torch.ones(args.copy_probe_mib * (1 << 18), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    edges_per_s = w.nnz * args.steps / elapsed
+
+    # per-launch HIP-event timing (events on the launch stream) over the same number of steps
+    gta.gta_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    records = gta.gta_profile_read(reset=True)
+    gta.gta_profile_enable(False)
+    row_bytes = w.heads * w.head_dim * (4 if w.dtype == "f32" else 2)
+    kernels: dict = {}
+    for r in records:
+        k = kernels.setdefault(r["name"], {"ms": 0.0, "launches": 0, "rows": r["rows"], "entries": r["entries"]})
+        k["ms"] += r["ms"]
+        k["launches"] += 1
+    total_bytes = 0
+    for name, k in kernels.items():
+        k["avg_ms"] = k["ms"] / k["launches"]
+        pass_name, sched = name.rsplit(".", 1)
+        rows = k["rows"] if sched != "chunk" else int(plan.info().n_chunked[0 if pass_name != "bwd_src" else 1])
+        k["bytes"] = 0 if sched == "merge" else algorithmic_bytes(pass_name, rows, k["entries"], row_bytes, w.heads)
+        k["gbs"] = k["bytes"] / (k["avg_ms"] * 1e-3) / 1e9 if k["avg_ms"] > 0 else 0.0
+        total_bytes += k["bytes"]
+        log(f"  {name:16s} {k['avg_ms']:9.3f} ms  rows={rows:9d} entries={k['entries']:10d}  "
+            f"{k['bytes'] / 1e9:8.3f} GB  {k['gbs']:8.1f} GB/s")
+    dom_name, dom = max(kernels.items(), key=lambda kv: kv[1]["ms"])
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom_name))
+    result = {
+        "metric": "edges/sec, sparse graph attention fwd+bwd, 1 MI355X; achieved HBM GB/s",
+        "value": edges_per_s, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "recipe": w.recipe, "n_dst": w.n_dst, "n_src": w.n_src, "nnz": w.nnz,
+                   "heads": w.heads, "head_dim": w.head_dim, "accumulate": "f32",
+                   "plan_ms": plan_ms, "wave_max_deg": int(plan.info().wave_max_deg),
+                   "hub_chunk": int(plan.info().hub_chunk)},
+        "hbm": {"algorithmic_bytes_per_step": total_bytes,
+                "achieved_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
+                "frac_of_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "kernels": {n: {"avg_ms": round(k["avg_ms"], 4), "gbs": round(k["gbs"], 1)} for n, k in kernels.items()},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": dom["bytes"], "avg_launch_ms": dom["avg_ms"]},
+    }
+    if not args.no_cpu_baseline:
+        del Q, K, V, dO, out, dQ, dK, dV
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_edges)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
