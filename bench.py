@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # (see profiles/), keyed by (workload, kernel); absent = not measured.
 MEASURED_TRAFFIC_BYTES: dict = {
     # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, scale factors from the copy probe
-    ("large", "bwd_src.wave"): int((24510167 * 2.0 + 1618080 * 1.0) * 1024),
+    ("large", "bwd_src"): int((35988903 * 2.0 + 2457859 * 1.0) * 1024),
 }
 
 
@@ -145,28 +145,35 @@ def main() -> int:
     edges_per_s = w.nnz * args.steps / elapsed
 
     # per-launch HIP-event timing (events on the launch stream) over the same number of steps
-    gta.gta_profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    records = gta.gta_profile_read(reset=True)
-    gta.gta_profile_enable(False)
     row_bytes = w.heads * w.head_dim * (4 if w.dtype == "f32" else 2)
-    kernels: dict = {}
-    for r in records:
-        k = kernels.setdefault(r["name"], {"ms": 0.0, "launches": 0, "rows": r["rows"], "entries": r["entries"]})
-        k["ms"] += r["ms"]
-        k["launches"] += 1
-    total_bytes = 0
-    for name, k in kernels.items():
-        k["avg_ms"] = k["ms"] / k["launches"]
-        pass_name, sched = name.rsplit(".", 1)
-        rows = k["rows"] if sched != "chunk" else int(plan.info().n_chunked[0 if pass_name != "bwd_src" else 1])
-        k["bytes"] = 0 if sched == "merge" else algorithmic_bytes(pass_name, rows, k["entries"], row_bytes, w.heads)
-        k["gbs"] = k["bytes"] / (k["avg_ms"] * 1e-3) / 1e9 if k["avg_ms"] > 0 else 0.0
-        total_bytes += k["bytes"]
-        log(f"  {name:16s} {k['avg_ms']:9.3f} ms  rows={rows:9d} entries={k['entries']:10d}  "
-            f"{k['bytes'] / 1e9:8.3f} GB  {k['gbs']:8.1f} GB/s")
+
+    def timed_launches(mode):
+        gta.gta_profile_enable(mode)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        records = gta.gta_profile_read(reset=True)
+        gta.gta_profile_enable(0)
+        table: dict = {}
+        for r in records:
+            k = table.setdefault(r["name"], {"ms": 0.0, "launches": 0, "rows": r["rows"], "entries": r["entries"]})
+            k["ms"] += r["ms"]
+            k["launches"] += 1
+        for name, k in table.items():
+            k["avg_ms"] = k["ms"] / k["launches"]
+            parts = name.split(".")
+            k["bytes"] = 0 if parts[-1] == "merge" else algorithmic_bytes(parts[0], k["rows"], k["entries"],
+                                                                          row_bytes, w.heads)
+            k["gbs"] = k["bytes"] / (k["avg_ms"] * 1e-3) / 1e9 if k["avg_ms"] > 0 else 0.0
+            log(f"  {name:16s} {k['avg_ms']:9.3f} ms  rows={k['rows']:9d} entries={k['entries']:10d}  "
+                f"{k['bytes'] / 1e9:8.3f} GB  {k['gbs']:8.1f} GB/s")
+        return table
+
+    kernels = timed_launches(1)
+    total_bytes = sum(k["bytes"] for k in kernels.values())
+    if args.verbose:
+        log("  per-schedule launches (separate grids):")
+        timed_launches(2)
     dom_name, dom = max(kernels.items(), key=lambda kv: kv[1]["ms"])
     traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom_name))
     result = {

@@ -131,14 +131,15 @@ gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32
                         int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
                         float scale, void* scratch, size_t scratch_bytes, void* stream);
 
-/* Per-launch timing for benchmarks.  While enabled, every kernel launch of gta_attn_fwd/bwd is
- * bracketed by HIP events on the call's stream.  gta_profile_read synchronises those events and
+/* Per-launch timing for benchmarks.  While enabled (on = 1), every kernel launch of
+ * gta_attn_fwd/bwd is bracketed by HIP events on the call's stream.  on = 2 additionally launches
+ * the three row schedules of a pass separately (instead of in one grid) so each is timed alone.  gta_profile_read synchronises those events and
  * copies up to `cap` records to HOST memory (oldest first), returns how many launches were
  * recorded since the last reset, and clears the list when reset != 0. */
 typedef struct {
-    char name[40];   /* kernel family, e.g. "fwd.wave" */
+    char name[40];   /* "fwd", "bwd_dst", "bwd_src" (+ ".merge"; with on = 2: ".chunk", ".wave", ".packed") */
     float ms;        /* elapsed time of this launch     */
-    int64_t rows;    /* rows (or chunks) it processed   */
+    int64_t rows;    /* rows it processed               */
     int64_t entries; /* stored entries it processed     */
 } gta_launch_record;
 gta_status gta_profile_enable(int on);

@@ -212,8 +212,9 @@ def gta_attn_bwd(plan: Plan, Q, K, V, out, lse, dOut, scale: float = 0.0, dQ=Non
     return dQ, dK, dV
 
 
-def gta_profile_enable(on: bool):
-    _check(load_library().gta_profile_enable(int(bool(on))))
+def gta_profile_enable(on):
+    """0 = off, 1 = time every launch, 2 = also launch the row schedules of a pass separately."""
+    _check(load_library().gta_profile_enable(int(on)))
 
 
 def gta_profile_read(reset: bool = True):

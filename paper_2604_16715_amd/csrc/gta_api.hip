@@ -30,7 +30,10 @@ struct Record {
 std::mutex g_prof_mutex;
 std::vector<Record> g_records;
 bool g_profiling = false;
+bool g_split = false;
 }  // namespace
+
+bool split_launches() { return g_split; }
 
 LaunchTimer::LaunchTimer(const char* name, int64_t rows, int64_t entries, hipStream_t st)
     : slot(-1), stream(st) {
@@ -213,6 +216,7 @@ extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* 
 extern "C" GTA_API gta_status gta_profile_enable(int on) {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     g_profiling = on != 0;
+    g_split = on == 2;
     return GTA_OK;
 }
 

@@ -68,6 +68,8 @@ struct LaunchTimer {   // RAII: records events around one launch when profiling 
     hipStream_t stream;
 };
 
+bool split_launches();   // true while per-schedule timing (profile mode 2) is requested
+
 // ---- shape handling ---------------------------------------------------------------------
 struct Shape {
     int heads, head_dim, elem_bytes;

@@ -137,11 +137,13 @@ template <class Pass> __device__ __forceinline__ void wave_merge(float (&f)[Pass
 }
 
 // ---------------------------------------------------------------- schedules
+// Each schedule is a device function of the block index inside its own range, so one launch can
+// run all three back to back (longest rows first) or each can be launched by itself.
 template <class Pass>
-__global__ void __launch_bounds__(kBlockThreads) k_packed(typename Pass::Params prm, RowSet rs) {
+__device__ __forceinline__ void body_packed(const typename Pass::Params& prm, const RowSet& rs, int64_t block) {
     constexpr int G = Pass::G, W = 64 / G;
     const int lane = threadIdx.x & 63, g = lane / G, lig = lane % G;
-    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t wave = block * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t r = rs.begin + wave * W + g;
     const bool active = r < rs.end;
     int row = 0, b = 0, e = 0;
@@ -161,10 +163,10 @@ __global__ void __launch_bounds__(kBlockThreads) k_packed(typename Pass::Params 
 }
 
 template <class Pass>
-__global__ void __launch_bounds__(kBlockThreads) k_wave(typename Pass::Params prm, RowSet rs) {
+__device__ __forceinline__ void body_wave(const typename Pass::Params& prm, const RowSet& rs, int64_t block) {
     constexpr int G = Pass::G, W = 64 / G;
     const int lane = threadIdx.x & 63, g = lane / G, lig = lane % G;
-    const int64_t r = rs.begin + (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t r = rs.begin + block * kWavesPerBlock + (threadIdx.x >> 6);
     if (r >= rs.end) return;
     const int row = rs.rows[r];
     const int b = (int)rs.ptr[row], e = (int)rs.ptr[row + 1];
@@ -180,11 +182,11 @@ __global__ void __launch_bounds__(kBlockThreads) k_wave(typename Pass::Params pr
 }
 
 template <class Pass>
-__global__ void __launch_bounds__(kBlockThreads) k_chunk(typename Pass::Params prm, ChunkSet cs) {
+__device__ __forceinline__ void body_chunk(const typename Pass::Params& prm, const ChunkSet& cs, int64_t block,
+                                           float (*red)[Pass::N][Pass::G]) {
     constexpr int G = Pass::G, W = 64 / G, N = Pass::N;
-    __shared__ float red[kWavesPerBlock - 1][N][G];
     const int lane = threadIdx.x & 63, g = lane / G, lig = lane % G, w = threadIdx.x >> 6;
-    const int4 ch = cs.chunks[blockIdx.x];
+    const int4 ch = cs.chunks[block];
     const int row = ch.x, cb = ch.y, ce = ch.z;
     const bool first_chunk = (int64_t)cb == cs.ptr[row];
     Pass ps;
@@ -211,11 +213,37 @@ __global__ void __launch_bounds__(kBlockThreads) k_chunk(typename Pass::Params p
         if (ch.w == 1) {
             Pass::finish(prm, row, lig, ps.f);
         } else {
-            float* slot = prm.partial + (int64_t)blockIdx.x * (N * G);
+            float* slot = prm.partial + block * (N * G);
 #pragma unroll
             for (int i = 0; i < N; ++i) slot[i * G + lig] = ps.f[i];
         }
     }
+}
+
+template <class Pass>
+__global__ void __launch_bounds__(kBlockThreads) k_packed(typename Pass::Params prm, RowSet rs) {
+    body_packed<Pass>(prm, rs, blockIdx.x);
+}
+template <class Pass>
+__global__ void __launch_bounds__(kBlockThreads) k_wave(typename Pass::Params prm, RowSet rs) {
+    body_wave<Pass>(prm, rs, blockIdx.x);
+}
+template <class Pass>
+__global__ void __launch_bounds__(kBlockThreads) k_chunk(typename Pass::Params prm, ChunkSet cs) {
+    __shared__ float red[kWavesPerBlock - 1][Pass::N][Pass::G];
+    body_chunk<Pass>(prm, cs, blockIdx.x, red);
+}
+
+// all three schedules in one grid: blocks [0, n_chunks) run chunks, the next wave_blocks run
+// one row per wavefront, the rest run packed rows
+struct FusedRanges { int64_t wave_blocks; RowSet wave, packed; };
+template <class Pass>
+__global__ void __launch_bounds__(kBlockThreads) k_rows(typename Pass::Params prm, ChunkSet cs, FusedRanges fr) {
+    __shared__ float red[kWavesPerBlock - 1][Pass::N][Pass::G];
+    const int64_t b = blockIdx.x;
+    if (b < cs.n_chunks) body_chunk<Pass>(prm, cs, b, red);
+    else if (b < cs.n_chunks + fr.wave_blocks) body_wave<Pass>(prm, fr.wave, b - cs.n_chunks);
+    else body_packed<Pass>(prm, fr.packed, b - cs.n_chunks - fr.wave_blocks);
 }
 
 // rows that were cut into several chunks: combine their partial results in chunk order
@@ -242,6 +270,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_merge(typename Pass::Params p
 }
 
 // ---------------------------------------------------------------- launching a pass
+// One launch covers every row of the side (plus the small merge launch when hub rows exist).
+// With split timing requested each schedule gets its own launch so it can be timed by itself.
 template <class Pass>
 gta_status launch_pass(const char* name, const typename Pass::Params& prm, const gta_plan* plan, int side,
                        hipStream_t st) {
@@ -249,34 +279,44 @@ gta_status launch_pass(const char* name, const typename Pass::Params& prm, const
     const Side& sd = plan->side[side];
     const Split sp = make_split(plan, side, Pass::G);
     char label[40];
-    if (sd.n_chunks > 0) {   // longest rows first
-        ChunkSet cs{sd.ptr, sd.idx, sd.chunks, sd.chunk_ptr, sd.bin_rows, sd.n_chunks, sd.n_hub};
-        {
+    ChunkSet cs{sd.ptr, sd.idx, sd.chunks, sd.chunk_ptr, sd.bin_rows, sd.n_chunks, sd.n_hub};
+    const RowSet wave{sd.ptr, sd.idx, sd.bin_rows, sp.wave_begin, sp.wave_end};
+    const RowSet packed{sd.ptr, sd.idx, sd.bin_rows, sp.pack_begin, sp.pack_end};
+    const int64_t wave_blocks = (sp.wave_end - sp.wave_begin + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t per_block = kWavesPerBlock * W;
+    const int64_t pack_blocks = (sp.pack_end - sp.pack_begin + per_block - 1) / per_block;
+    const int64_t merge_blocks = (sd.n_hub + per_block - 1) / per_block;
+    auto merge = [&]() {
+        if (sd.n_hub <= 0) return;
+        snprintf(label, sizeof label, "%s.merge", name);
+        LaunchTimer t(label, sd.n_hub, 0, st);
+        hipLaunchKernelGGL(k_merge<Pass>, dim3((unsigned)merge_blocks), dim3(kBlockThreads), 0, st, prm, cs);
+    };
+    if (!split_launches()) {
+        const int64_t blocks = sd.n_chunks + wave_blocks + pack_blocks;
+        if (blocks > 0) {
+            LaunchTimer t(name, sd.n_rows, sp.chunk_entries + sp.wave_entries + sp.pack_entries, st);
+            hipLaunchKernelGGL(k_rows<Pass>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st, prm, cs,
+                               FusedRanges{wave_blocks, wave, packed});
+        }
+        merge();
+    } else {
+        if (sd.n_chunks > 0) {
             snprintf(label, sizeof label, "%s.chunk", name);
-            LaunchTimer t(label, sd.n_chunks, sp.chunk_entries, st);
+            LaunchTimer t(label, sd.n_chunked, sp.chunk_entries, st);
             hipLaunchKernelGGL(k_chunk<Pass>, dim3((unsigned)sd.n_chunks), dim3(kBlockThreads), 0, st, prm, cs);
         }
-        if (sd.n_hub > 0) {
-            snprintf(label, sizeof label, "%s.merge", name);
-            LaunchTimer t(label, sd.n_hub, 0, st);
-            const int64_t blocks = (sd.n_hub + kWavesPerBlock * W - 1) / (kWavesPerBlock * W);
-            hipLaunchKernelGGL(k_merge<Pass>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st, prm, cs);
+        merge();
+        if (wave_blocks > 0) {
+            snprintf(label, sizeof label, "%s.wave", name);
+            LaunchTimer t(label, sp.wave_end - sp.wave_begin, sp.wave_entries, st);
+            hipLaunchKernelGGL(k_wave<Pass>, dim3((unsigned)wave_blocks), dim3(kBlockThreads), 0, st, prm, wave);
         }
-    }
-    if (sp.wave_end > sp.wave_begin) {
-        RowSet rs{sd.ptr, sd.idx, sd.bin_rows, sp.wave_begin, sp.wave_end};
-        snprintf(label, sizeof label, "%s.wave", name);
-        LaunchTimer t(label, sp.wave_end - sp.wave_begin, sp.wave_entries, st);
-        const int64_t blocks = (sp.wave_end - sp.wave_begin + kWavesPerBlock - 1) / kWavesPerBlock;
-        hipLaunchKernelGGL(k_wave<Pass>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st, prm, rs);
-    }
-    if (sp.pack_end > sp.pack_begin) {
-        RowSet rs{sd.ptr, sd.idx, sd.bin_rows, sp.pack_begin, sp.pack_end};
-        snprintf(label, sizeof label, "%s.packed", name);
-        LaunchTimer t(label, sp.pack_end - sp.pack_begin, sp.pack_entries, st);
-        const int64_t per_block = kWavesPerBlock * W;
-        const int64_t blocks = (sp.pack_end - sp.pack_begin + per_block - 1) / per_block;
-        hipLaunchKernelGGL(k_packed<Pass>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st, prm, rs);
+        if (pack_blocks > 0) {
+            snprintf(label, sizeof label, "%s.packed", name);
+            LaunchTimer t(label, sp.pack_end - sp.pack_begin, sp.pack_entries, st);
+            hipLaunchKernelGGL(k_packed<Pass>, dim3((unsigned)pack_blocks), dim3(kBlockThreads), 0, st, prm, packed);
+        }
     }
     GTA_HIP_TRY(hipGetLastError());
     return GTA_OK;
