@@ -25,19 +25,27 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # (see profiles/), keyed by (workload, kernel); absent = not measured.
 MEASURED_TRAFFIC_BYTES: dict = {
     # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, scale factors from the copy probe
-    ("large", "bwd_src"): int((35988903 * 2.0 + 2457859 * 1.0) * 1024),
+    ("large", "bwd_src"): int((36005466 * 2.0 + 4610323 * 1.0) * 1024),
 }
 
 
-def algorithmic_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int) -> int:
+def algorithmic_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int, lean: bool) -> int:
     """Bytes the method must move for `rows` rows holding `entries` stored entries: every entry
-    gathers its rows (no reuse assumed), streams are touched once."""
+    gathers its rows (no reuse assumed), streams are touched once.  `lean` = the backward form that
+    keeps nothing per stored entry."""
     R, H = row_bytes, heads
-    if pass_name == "fwd":       # K,V gathers + index | Q read, out write, lse write, row pointer
+    if pass_name == "fwd":          # K,V gathers + index | Q read, out write, lse write, row pointer
         return entries * (2 * R + 4) + rows * (2 * R + 4 * H + 8)
-    if pass_name == "bwd_dst":   # K,V gathers + index | Q,dO,out read, dQ write, lse read, stats write
+    if pass_name == "bwd_rowstat":  # Y, dY read, lse read, (lse, delta) write
+        return rows * (2 * R + 12 * H)
+    if pass_name == "bwd_src" and not lean:
+        # Q,dY gathers + (lse, delta) + destination id + stored position + dZ write | K,V read, dK,dV write
+        return entries * (2 * R + 8 * H + 8 + 4 * H) + rows * (4 * R + 8)
+    if pass_name == "bwd_dq":       # K gather + index + dZ read | dQ write, row pointer
+        return entries * (R + 4 + 4 * H) + rows * (R + 8)
+    if pass_name == "bwd_dst":      # K,V gathers + index | Q,dY,Y read, dQ write, lse read, stats write
         return entries * (2 * R + 4) + rows * (4 * R + 12 * H + 8)
-    if pass_name == "bwd_src":   # Q,dO gathers + stats + index | K,V read, dK,dV write, row pointer
+    if pass_name == "bwd_src":      # Q,dY gathers + (lse, delta) + destination id | K,V read, dK,dV write
         return entries * (2 * R + 8 * H + 4) + rows * (4 * R + 8)
     raise KeyError(pass_name)
 
@@ -67,6 +75,50 @@ def cpu_baseline(w, sample_edges: int) -> dict:
                       f"renumbered) of workload '{w.name}', fp64 forward {t1 - t0:.2f}s + backward {t2 - t1:.2f}s"}
 
 
+def time_unfused(gta, torch, plan, Q, K, V, dO, w, steps, log) -> dict:
+    """The paper's decomposition (Section 2.2): forward SDDMM + softmax + SpMM, backward 3 SpMM +
+    1 SDDMM + softmax backward, with Z, U, dU, dZ stored as float [nnz, heads]."""
+    scale = 1.0 / float(np.sqrt(w.head_dim))
+    E, H = w.nnz, w.heads
+    Z = torch.empty((E, H), dtype=torch.float32, device=Q.device)
+    U, dU, dZ = torch.empty_like(Z), torch.empty_like(Z), torch.empty_like(Z)
+    lse = torch.empty((w.n_dst, H), dtype=torch.float32, device=Q.device)
+    Y, dQ = torch.empty_like(Q), torch.empty_like(Q)
+    dK, dV = torch.empty_like(K), torch.empty_like(V)
+
+    def step():
+        gta.gta_sddmm(plan, Q, K, Z)
+        gta.gta_edge_softmax(plan, Z, scale, U, lse)
+        gta.gta_spmm(plan, U, V, False, Y)
+        gta.gta_spmm(plan, U, dO, True, dV)
+        gta.gta_sddmm(plan, dO, V, dU)
+        gta.gta_edge_softmax_bwd(plan, U, dU, scale, dZ)
+        gta.gta_spmm(plan, dZ, K, False, dQ)
+        gta.gta_spmm(plan, dZ, Q, True, dK)
+
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    gta.gta_profile_enable(1)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    recs = gta.gta_profile_read(reset=True)
+    gta.gta_profile_enable(0)
+    per_op: dict = {}
+    for r in recs:
+        per_op[r["name"]] = per_op.get(r["name"], 0.0) + r["ms"] / steps
+    for k, v in per_op.items():
+        log(f"  unfused {k:20s} {v:9.3f} ms per step")
+    return {"ms_per_step": ms, "edges_per_s": E / (ms * 1e-3),
+            "op_ms_per_step": {k: round(v, 4) for k, v in per_op.items()},
+            "note": "per step: 2 sddmm, 2 spmm, 2 spmm_t, 1 edge_softmax, 1 edge_softmax_bwd launches"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +134,10 @@ def main() -> int:
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain elementwise copy kernel (reads and writes this many MiB) "
                          "so that profiler byte counters can be scaled against a known size")
+    ap.add_argument("--lean-scratch", action="store_true",
+                    help="give the backward only the minimum scratch (nothing kept per stored entry)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="also time the paper's operator-by-operator decomposition (SDDMM, softmax, SpMM ...)")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -124,7 +180,7 @@ def main() -> int:
 
     def step():
         gta.gta_attn_fwd(plan, Q, K, V, 0.0, out, lse)
-        gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO, 0.0, dQ, dK, dV)
+        gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO, 0.0, dQ, dK, dV, lean_scratch=args.lean_scratch)
 
     if args.copy_probe_mib > 0:   # calibration kernel for rocprofv3 --pmc runs (outside the timed region)
         src = torch.ones(args.copy_probe_mib * (1 << 18), dtype=torch.float32, device=dev)
@@ -163,7 +219,7 @@ def main() -> int:
             k["avg_ms"] = k["ms"] / k["launches"]
             parts = name.split(".")
             k["bytes"] = 0 if parts[-1] == "merge" else algorithmic_bytes(parts[0], k["rows"], k["entries"],
-                                                                          row_bytes, w.heads)
+                                                                          row_bytes, w.heads, args.lean_scratch)
             k["gbs"] = k["bytes"] / (k["avg_ms"] * 1e-3) / 1e9 if k["avg_ms"] > 0 else 0.0
             log(f"  {name:16s} {k['avg_ms']:9.3f} ms  rows={k['rows']:9d} entries={k['entries']:10d}  "
                 f"{k['bytes'] / 1e9:8.3f} GB  {k['gbs']:8.1f} GB/s")
@@ -183,6 +239,7 @@ def main() -> int:
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "recipe": w.recipe, "n_dst": w.n_dst, "n_src": w.n_src, "nnz": w.nnz,
                    "heads": w.heads, "head_dim": w.head_dim, "accumulate": "f32",
+                   "backward": "recompute-per-entry" if args.lean_scratch else "dZ-kept-per-entry",
                    "plan_ms": plan_ms, "wave_max_deg": int(plan.info().wave_max_deg),
                    "hub_chunk": int(plan.info().hub_chunk)},
         "hbm": {"algorithmic_bytes_per_step": total_bytes,
@@ -193,6 +250,8 @@ def main() -> int:
                      "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": dom["bytes"], "avg_launch_ms": dom["avg_ms"]},
     }
+    if args.unfused:
+        result["unfused"] = time_unfused(gta, torch, plan, Q, K, V, dO, w, args.steps, log)
     if not args.no_cpu_baseline:
         del Q, K, V, dO, out, dQ, dK, dV
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_edges)

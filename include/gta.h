@@ -62,12 +62,17 @@ typedef struct gta_plan gta_plan; /* opaque, host-side handle */
  *                                       chunk; rows with more than one chunk are merged afterwards
  *   pack_max_deg                      : rows up to this degree are packed several to a wavefront
  *                                       (0 = chosen per shape at launch)
- *   validate                          : 1 = check indptr / indices at plan creation            */
+ *   validate                          : 1 = check indptr / indices at plan creation
+ *   keep_dz_min_nnz                   : the backward keeps dZ per stored entry (needs the recommended
+ *                                       scratch size) only for graphs with at least this many entries;
+ *                                       0 = default (262144: below that the extra launch costs more
+ *                                       than the saved gathers), 1 = always, negative = never          */
 typedef struct {
     int32_t pack_max_deg;
     int32_t wave_max_deg;
     int32_t hub_chunk;
     int32_t validate;
+    int32_t keep_dz_min_nnz;
 } gta_plan_opts;
 
 #define GTA_NUM_CLASSES 33 /* degree classes: 0 for degree 0, else 1 + ceil(log2(degree)) */
@@ -110,9 +115,15 @@ gta_status gta_plan_export_bins(const gta_plan* plan, int side, int32_t* bin_row
 gta_status gta_plan_export_transpose(const gta_plan* plan, int64_t* t_indptr, int32_t* t_indices,
                                      int32_t* t_eid);
 
-/* Bytes of device scratch gta_attn_fwd / gta_attn_bwd need (partial results of split rows and
- * the per-row statistics of the backward pass).  0 on bad args. */
+/* Bytes of device scratch for gta_attn_fwd / gta_attn_bwd (0 on bad args).
+ * gta_attn_scratch_bytes     : recommended size.  Besides the partial results of split rows and the
+ *                              per-row statistics it holds dZ as float [nnz, heads], which lets the
+ *                              backward gather three rows per entry instead of four.
+ * gta_attn_scratch_bytes_min : smallest size accepted.  With less than the recommended size the
+ *                              backward keeps nothing per entry and recomputes dZ in both of its
+ *                              passes (same results up to rounding, about 20 % slower).           */
 size_t gta_attn_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
+size_t gta_attn_scratch_bytes_min(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
 
 /* Forward (Eq. 4-5 fused: SDDMM -> edge softmax -> SpMM, scores never stored).
  * scale <= 0 selects 1/sqrt(head_dim).  Writes every row of out and lse. */
@@ -130,6 +141,29 @@ gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32
                         const float* lse, const void* dOut, void* dQ, void* dK, void* dV,
                         int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
                         float scale, void* scratch, size_t scratch_bytes, void* stream);
+
+/* ---- The same computation as separate operators (Section 2.2 counts them: forward = 1 SDDMM +
+ * softmax + 1 SpMM, backward = 3 SpMM + 1 SDDMM), with the per-entry matrices stored as
+ * float [nnz, heads] in the order of `indices`.  Not used by gta_attn_fwd/bwd; provided so the
+ * unfused decomposition can be run and timed operator by operator.  scratch: as for gta_attn_fwd.
+ *
+ * gta_sddmm:            Z[e,h]  = sum_d X[i,h,d] * Y[j,h,d]          X [n_dst,H,D], Y [n_src,H,D]
+ * gta_edge_softmax:     U[e,h]  = softmax over row i of scale*Z[.,h]; lse (may be NULL) [n_dst,H]
+ * gta_edge_softmax_bwd: dZ[e,h] = scale * U[e,h] * (dU[e,h] - sum_{e' in row i} U[e',h] dU[e',h])
+ * gta_spmm:   transposed = 0:  Y[i,h,:] = sum_{e=(i<-j)} W[e,h] * X[j,h,:]   X [n_src,..], Y [n_dst,..]
+ *             transposed = 1:  Y[j,h,:] = sum_{e=(i<-j)} W[e,h] * X[i,h,:]   X [n_dst,..], Y [n_src,..]
+ *             (terms of a row are added in the plan's fixed order; no atomics)                      */
+gta_status gta_sddmm(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, const void* X,
+                     const void* Y, float* Z, int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                     gta_dtype dtype, void* scratch, size_t scratch_bytes, void* stream);
+gta_status gta_edge_softmax(const gta_plan* plan, const int64_t* indptr, const float* Z, float* U,
+                            float* lse, int64_t n_dst, int heads, float scale, void* stream);
+gta_status gta_edge_softmax_bwd(const gta_plan* plan, const int64_t* indptr, const float* U,
+                                const float* dU, float* dZ, int64_t n_dst, int heads, float scale,
+                                void* stream);
+gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, const float* W,
+                    const void* X, void* Y, int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                    gta_dtype dtype, int transposed, void* scratch, size_t scratch_bytes, void* stream);
 
 /* Per-launch timing for benchmarks.  While enabled (on = 1), every kernel launch of
  * gta_attn_fwd/bwd is bracketed by HIP events on the call's stream.  on = 2 additionally launches

@@ -94,3 +94,68 @@ def backward(indptr, indices, Q, K, V, dY, scale=None, grouped=True):
                      Q.ctypes.data, K.ctypes.data, V.ctypes.data, dY.ctypes.data,
                      dQ.ctypes.data, dK.ctypes.data, dV.ctypes.data, int(bool(grouped)))
     return dQ, dK, dV
+
+
+# ---- the individual operators (same functions forward() / backward() are composed of) -------
+def _op_protos(lib):
+    i64, ci, dbl, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+    lib.sga_sddmm.restype = None
+    lib.sga_sddmm.argtypes = [i64, vp, vp, ci, ci, vp, vp, vp]
+    lib.sga_edge_softmax.restype = None
+    lib.sga_edge_softmax.argtypes = [i64, vp, ci, dbl, vp, vp, vp]
+    lib.sga_edge_softmax_bwd.restype = None
+    lib.sga_edge_softmax_bwd.argtypes = [i64, vp, ci, dbl, vp, vp, vp]
+    lib.sga_spmm.restype = None
+    lib.sga_spmm.argtypes = [i64, vp, vp, ci, ci, vp, vp, vp]
+    lib.sga_spmm_t.restype = None
+    lib.sga_spmm_t.argtypes = [i64, i64, vp, vp, ci, ci, vp, vp, vp]
+    return lib
+
+
+def sddmm(indptr, indices, X, Y):
+    """Z [E,H]: per stored entry (i <- j) and head, the dot product of X[i,h] and Y[j,h]."""
+    lib = _op_protos(_load())
+    indptr, indices = _graph(indptr, indices)
+    X, Y = _f64(X), _f64(Y)
+    n_dst, H, D = X.shape
+    Z = np.empty((int(indptr[-1]), H), dtype=np.float64)
+    lib.sga_sddmm(n_dst, indptr.ctypes.data, indices.ctypes.data, H, D, X.ctypes.data, Y.ctypes.data, Z.ctypes.data)
+    return Z
+
+
+def edge_softmax(indptr, Z, scale):
+    lib = _op_protos(_load())
+    indptr = np.ascontiguousarray(indptr, dtype=np.int64)
+    Z = _f64(Z)
+    n_dst, H = indptr.shape[0] - 1, Z.shape[1]
+    U = np.zeros_like(Z)
+    lse = np.empty((n_dst, H), dtype=np.float64)
+    lib.sga_edge_softmax(n_dst, indptr.ctypes.data, H, float(scale), Z.ctypes.data, U.ctypes.data, lse.ctypes.data)
+    return U, lse
+
+
+def edge_softmax_bwd(indptr, U, dU, scale):
+    lib = _op_protos(_load())
+    indptr = np.ascontiguousarray(indptr, dtype=np.int64)
+    U, dU = _f64(U), _f64(dU)
+    dZ = np.zeros_like(U)
+    lib.sga_edge_softmax_bwd(indptr.shape[0] - 1, indptr.ctypes.data, U.shape[1], float(scale), U.ctypes.data,
+                             dU.ctypes.data, dZ.ctypes.data)
+    return dZ
+
+
+def spmm(indptr, indices, W, X, n_src=None, transposed=False):
+    """transposed=False: Y[i] = sum_e W[e] X[j];  transposed=True: Y[j] = sum_e W[e] X[i] (serial scatter)."""
+    lib = _op_protos(_load())
+    indptr, indices = _graph(indptr, indices)
+    W, X = _f64(W), _f64(X)
+    n_dst = indptr.shape[0] - 1
+    _, H, D = X.shape
+    if not transposed:
+        Y = np.empty((n_dst, H, D), dtype=np.float64)
+        lib.sga_spmm(n_dst, indptr.ctypes.data, indices.ctypes.data, H, D, W.ctypes.data, X.ctypes.data, Y.ctypes.data)
+    else:
+        Y = np.empty((n_src, H, D), dtype=np.float64)
+        lib.sga_spmm_t(n_dst, n_src, indptr.ctypes.data, indices.ctypes.data, H, D, W.ctypes.data, X.ctypes.data,
+                       Y.ctypes.data)
+    return Y

@@ -22,7 +22,7 @@ class GtaError(RuntimeError):
 
 class _PlanOpts(Structure):
     _fields_ = [("pack_max_deg", c_int32), ("wave_max_deg", c_int32), ("hub_chunk", c_int32),
-                ("validate", c_int32)]
+                ("validate", c_int32), ("keep_dz_min_nnz", c_int32)]
 
 
 class _PlanInfo(Structure):
@@ -65,12 +65,23 @@ def load_library():
     lib.gta_plan_export_transpose.argtypes = [vp, vp, vp, vp]
     lib.gta_attn_scratch_bytes.restype = c_size_t
     lib.gta_attn_scratch_bytes.argtypes = [vp, c_int, c_int, c_int]
+    lib.gta_attn_scratch_bytes_min.restype = c_size_t
+    lib.gta_attn_scratch_bytes_min.argtypes = [vp, c_int, c_int, c_int]
     lib.gta_attn_fwd.restype = c_int
     lib.gta_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int,
                                  c_float, vp, c_size_t, vp]
     lib.gta_attn_bwd.restype = c_int
     lib.gta_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int,
                                  c_int, c_int, c_float, vp, c_size_t, vp]
+    lib.gta_sddmm.restype = c_int
+    lib.gta_sddmm.argtypes = [vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
+    lib.gta_edge_softmax.restype = c_int
+    lib.gta_edge_softmax.argtypes = [vp, vp, vp, vp, vp, c_int64, c_int, c_float, vp]
+    lib.gta_edge_softmax_bwd.restype = c_int
+    lib.gta_edge_softmax_bwd.argtypes = [vp, vp, vp, vp, vp, c_int64, c_int, c_float, vp]
+    lib.gta_spmm.restype = c_int
+    lib.gta_spmm.argtypes = [vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int, c_int, vp,
+                             c_size_t, vp]
     lib.gta_profile_enable.restype = c_int
     lib.gta_profile_enable.argtypes = [c_int]
     lib.gta_profile_read.restype = c_int
@@ -149,10 +160,10 @@ class Plan:
                                                         t_indices.ctypes.data, t_eid.ctypes.data))
         return dict(t_indptr=t_indptr, t_indices=t_indices, t_eid=t_eid)
 
-    def scratch(self, heads: int, head_dim: int, dtype_code: int) -> torch.Tensor:
-        key = (heads, head_dim, dtype_code)
+    def scratch(self, heads: int, head_dim: int, dtype_code: int, lean: bool = False) -> torch.Tensor:
+        key = (heads, head_dim, dtype_code, lean)
         if key not in self._scratch:
-            nbytes = gta_attn_scratch_bytes(self, heads, head_dim, dtype_code)
+            nbytes = gta_attn_scratch_bytes(self, heads, head_dim, dtype_code, lean)
             if nbytes == 0:
                 raise GtaError(2, "unsupported shape for scratch query")
             self._scratch[key] = torch.empty(nbytes, dtype=torch.uint8, device=self.indptr.device)
@@ -160,7 +171,7 @@ class Plan:
 
 
 def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pack_max_deg=0,
-                    wave_max_deg=0, hub_chunk=0, validate=False) -> Plan:
+                    wave_max_deg=0, hub_chunk=0, validate=False, keep_dz_min_nnz=0) -> Plan:
     lib = load_library()
     if indptr.dtype != torch.int64 or indices.dtype != torch.int32:
         raise GtaError(1, "indptr must be int64 and indices int32")
@@ -168,7 +179,7 @@ def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pac
         raise GtaError(1, "graph tensors must be contiguous device tensors")
     n_dst = indptr.numel() - 1
     nnz = indices.numel()
-    opts = _PlanOpts(pack_max_deg, wave_max_deg, hub_chunk, int(bool(validate)))
+    opts = _PlanOpts(pack_max_deg, wave_max_deg, hub_chunk, int(bool(validate)), keep_dz_min_nnz)
     nbytes = lib.gta_plan_workspace_bytes(n_dst, n_src, nnz, ctypes.byref(opts))
     if nbytes == 0:
         raise GtaError(1, "bad sizes or plan options")
@@ -179,8 +190,11 @@ def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pac
     return Plan(handle, workspace, indptr, indices, n_dst, n_src)
 
 
-def gta_attn_scratch_bytes(plan: Plan, heads: int, head_dim: int, dtype_code: int) -> int:
-    return int(load_library().gta_attn_scratch_bytes(plan.handle, heads, head_dim, dtype_code))
+def gta_attn_scratch_bytes(plan: Plan, heads: int, head_dim: int, dtype_code: int, lean: bool = False) -> int:
+    """Recommended scratch size, or with lean=True the smallest accepted one."""
+    lib = load_library()
+    fn = lib.gta_attn_scratch_bytes_min if lean else lib.gta_attn_scratch_bytes
+    return int(fn(plan.handle, heads, head_dim, dtype_code))
 
 
 def gta_attn_fwd(plan: Plan, Q, K, V, scale: float = 0.0, out=None, lse=None):
@@ -198,18 +212,66 @@ def gta_attn_fwd(plan: Plan, Q, K, V, scale: float = 0.0, out=None, lse=None):
     return out, lse
 
 
-def gta_attn_bwd(plan: Plan, Q, K, V, out, lse, dOut, scale: float = 0.0, dQ=None, dK=None, dV=None):
+def gta_attn_bwd(plan: Plan, Q, K, V, out, lse, dOut, scale: float = 0.0, dQ=None, dK=None, dV=None,
+                 lean_scratch: bool = False):
+    """lean_scratch=True passes the minimum scratch, which selects the backward form that keeps
+    nothing per stored entry."""
     n_dst, heads, head_dim = Q.shape
     code = _dtype_code(Q)
     dQ = torch.empty_like(Q) if dQ is None else dQ
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
-    scratch = plan.scratch(heads, head_dim, code)
+    scratch = plan.scratch(heads, head_dim, code, lean_scratch)
     _check(load_library().gta_attn_bwd(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q), _ptr(K),
                                        _ptr(V), _ptr(out), _ptr(lse), _ptr(dOut), _ptr(dQ), _ptr(dK), _ptr(dV),
                                        n_dst, K.shape[0], heads, head_dim, code, scale, _ptr(scratch),
                                        scratch.numel(), _stream()))
     return dQ, dK, dV
+
+
+def gta_sddmm(plan: Plan, X, Y, Z=None):
+    """Z [nnz,H] float32 = per-entry, per-head dot products of X[dst] and Y[src]."""
+    n_dst, heads, head_dim = X.shape
+    code = _dtype_code(X)
+    if Z is None:
+        Z = torch.empty((plan.indices.numel(), heads), dtype=torch.float32, device=X.device)
+    scratch = plan.scratch(heads, head_dim, code)
+    _check(load_library().gta_sddmm(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(X), _ptr(Y), _ptr(Z),
+                                    n_dst, Y.shape[0], heads, head_dim, code, _ptr(scratch), scratch.numel(),
+                                    _stream()))
+    return Z
+
+
+def gta_edge_softmax(plan: Plan, Z, scale: float, U=None, lse=None):
+    heads = Z.shape[1]
+    U = torch.empty_like(Z) if U is None else U
+    if lse is None:
+        lse = torch.empty((plan.n_dst, heads), dtype=torch.float32, device=Z.device)
+    _check(load_library().gta_edge_softmax(plan.handle, _ptr(plan.indptr), _ptr(Z), _ptr(U), _ptr(lse),
+                                           plan.n_dst, heads, scale, _stream()))
+    return U, lse
+
+
+def gta_edge_softmax_bwd(plan: Plan, U, dU, scale: float, dZ=None):
+    heads = U.shape[1]
+    dZ = torch.empty_like(U) if dZ is None else dZ
+    _check(load_library().gta_edge_softmax_bwd(plan.handle, _ptr(plan.indptr), _ptr(U), _ptr(dU), _ptr(dZ),
+                                               plan.n_dst, heads, scale, _stream()))
+    return dZ
+
+
+def gta_spmm(plan: Plan, W, X, transposed: bool = False, Y=None):
+    """transposed=False: Y[dst] = sum W[e] X[src];  transposed=True: Y[src] = sum W[e] X[dst]."""
+    _, heads, head_dim = X.shape
+    code = _dtype_code(X)
+    rows_out = plan.n_src if transposed else plan.n_dst
+    if Y is None:
+        Y = torch.empty((rows_out, heads, head_dim), dtype=X.dtype, device=X.device)
+    scratch = plan.scratch(heads, head_dim, code)
+    _check(load_library().gta_spmm(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(W), _ptr(X), _ptr(Y),
+                                   plan.n_dst, plan.n_src, heads, head_dim, code, int(bool(transposed)),
+                                   _ptr(scratch), scratch.numel(), _stream()))
+    return Y
 
 
 def gta_profile_enable(on):

@@ -110,7 +110,9 @@ Split make_split(const gta_plan* plan, int side, int lanes_per_row) {
 
 namespace {
 
-struct ScratchLayout { size_t rowstat, partial, total; };
+// rowstat | partial | dS.  `lean` ends before dS: enough for the forward and for the backward form
+// that recomputes everything per entry; `total` also holds dS [nnz, heads] for the faster form.
+struct ScratchLayout { size_t rowstat, partial, dS, lean, total; };
 
 ScratchLayout scratch_layout(const gta_plan* plan, const Shape& sh) {
     ScratchLayout L;
@@ -120,7 +122,9 @@ ScratchLayout scratch_layout(const gta_plan* plan, const Shape& sh) {
     const size_t bsrc = (size_t)plan->side[1].n_chunks * G * (2 * nv);
     L.rowstat = 0;
     L.partial = up(sizeof(float2) * (size_t)plan->n_dst * (size_t)sh.heads);
-    L.total = L.partial + up(sizeof(float) * (fwd > bsrc ? fwd : bsrc)) + 256;
+    L.dS = L.partial + up(sizeof(float) * (fwd > bsrc ? fwd : bsrc)) + 256;
+    L.lean = L.dS;
+    L.total = L.dS + up(sizeof(float) * (size_t)plan->nnz * (size_t)sh.heads);
     return L;
 }
 
@@ -140,8 +144,8 @@ gta_status check_common(const gta_plan* plan, const int64_t* indptr, const int32
     *sl = scratch_layout(plan, *sh);
     if (!scratch) return fail(GTA_ERR_INVALID_ARG, "scratch is null");
     if (((uintptr_t)scratch & 255) != 0) return fail(GTA_ERR_INVALID_ARG, "scratch must be 256-byte aligned");
-    if (scratch_bytes < sl->total)
-        return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, sl->total);
+    if (scratch_bytes < sl->lean)
+        return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, at least %zu needed", scratch_bytes, sl->lean);
     return GTA_OK;
 }
 
@@ -156,6 +160,12 @@ extern "C" GTA_API size_t gta_attn_scratch_bytes(const gta_plan* plan, int heads
     Shape sh;
     if (!plan || make_shape(heads, head_dim, dtype, &sh) != GTA_OK) return 0;
     return scratch_layout(plan, sh).total;
+}
+
+extern "C" GTA_API size_t gta_attn_scratch_bytes_min(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype) {
+    Shape sh;
+    if (!plan || make_shape(heads, head_dim, dtype, &sh) != GTA_OK) return 0;
+    return scratch_layout(plan, sh).lean;
 }
 
 extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
@@ -205,6 +215,13 @@ extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* 
     a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
     a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
+    if (scratch_bytes >= sl.total && n_dst > 0 && plan->nnz >= plan->keep_dz_min_nnz) {
+        // dZ kept per stored entry: row statistics, then dK/dV (+ dZ), then dQ as an SpMM over K
+        a.dS = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.dS);
+        if ((rc = launch_rowstat(a)) != GTA_OK) return rc;
+        if ((rc = launch_bwd_src(a)) != GTA_OK) return rc;
+        return launch_bwd_dq(a);
+    }
     if (n_dst > 0) {
         rc = launch_bwd_dst(a);
         if (rc != GTA_OK) return rc;

@@ -4,7 +4,13 @@
 //     dZ = a * (dU - delta_i)               (softmax backward, delta_i = sum_e a_e dU_e = dY_i . Y_i)
 //     dQ_i += scale * dZ * k_j              (SpMM dQ = dZ K)
 // It also leaves (lse * log2 e, delta) per (row, head) for the source-major pass.
+//
+// Second form, used when the caller's scratch can hold dZ for every stored entry: a streaming
+// kernel writes (lse * log2 e, delta) first, the source-major pass computes dZ and stores it in
+// transposed order, and dQ is then a plain SpMM over the stored dZ that gathers K only (one row
+// gather per entry less).
 #include "gta_kernels.h"
+#include "gta_spmm_pass.h"
 
 namespace gta {
 namespace {
@@ -13,6 +19,7 @@ template <class T, int LH_, int G_>
 struct BwdDstPass {
     static constexpr int LH = LH_, G = G_, U = UnrollFor<G_>::value;
     static constexpr int NV = Elt<T>::NV;
+    static constexpr bool kUsesEntryId = false;
     static constexpr int N = NV;   // f = dQ accumulator (unscaled)
     struct Params {
         const char *Q, *K, *V, *out, *dO;
@@ -49,7 +56,7 @@ struct BwdDstPass {
         if (active && primary && lig % LH == 0)
             p.rowstat[(int64_t)row * p.heads + lig / LH] = make_float2(lse2, delta);
     }
-    __device__ __forceinline__ void load(const Params& p, int u, int j, bool ok, int lig) {
+    __device__ __forceinline__ void load(const Params& p, int u, int j, int, bool ok, int lig) {
         kr[u] = make_uint4(0, 0, 0, 0);
         vr[u] = make_uint4(0, 0, 0, 0);
         if (ok) {
@@ -86,6 +93,58 @@ struct BwdDstPass {
     }
 };
 
+// one group of G lanes per destination row, rows in natural order
+template <class T, int LH, int G>
+__global__ void __launch_bounds__(kBlockThreads)
+k_rowstat(const char* out, const char* dO, const float* lse, float2* rowstat, int64_t n_rows, int64_t stride,
+          int heads) {
+    constexpr int NV = Elt<T>::NV;
+    const int64_t row = ((int64_t)blockIdx.x * kBlockThreads + threadIdx.x) / G;
+    const int lig = threadIdx.x % G;
+    float d = 0.f;
+    if (row < n_rows) {
+        float o[NV], go[NV];
+        Elt<T>::unpack(load16(out, row, stride, lig), o);
+        Elt<T>::unpack(load16(dO, row, stride, lig), go);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) d = fmaf(go[i], o[i], d);
+    }
+    d = head_allreduce<LH>(d);
+    if (row < n_rows && lig % LH == 0)
+        rowstat[row * heads + lig / LH] = make_float2(lse[row * heads + lig / LH] * kLog2e, d);
+}
+
+template <class T> gta_status run_rowstat(const AttnArgs& a) {
+    const Shape& sh = a.shape;
+    const int64_t n = a.plan->n_dst;
+#define GTA_CALL(LHc, Gc)                                                                            \
+    {                                                                                                \
+        const int64_t blocks = (n * Gc + kBlockThreads - 1) / kBlockThreads;                         \
+        LaunchTimer t("bwd_rowstat", n, 0, a.stream);                                                \
+        hipLaunchKernelGGL((k_rowstat<T, LHc, Gc>), dim3((unsigned)blocks), dim3(kBlockThreads), 0,  \
+                           a.stream, (const char*)a.out, (const char*)a.dO, a.lse_in, a.rowstat, n,  \
+                           sh.row_bytes, sh.heads);                                                  \
+    }
+    GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
+#undef GTA_CALL
+    GTA_HIP_TRY(hipGetLastError());
+    return GTA_OK;
+}
+
+template <class T> gta_status run_dq(const AttnArgs& a) {
+    const Shape& sh = a.shape;
+#define GTA_CALL(LHc, Gc)                                                                            \
+    {                                                                                                \
+        using P = SpmmPass<T, LHc, Gc>;                                                              \
+        typename P::Params prm{a.dS, (const char*)a.K, (char*)a.dQ, a.partial, sh.row_bytes,         \
+                               a.scale, sh.heads};                                                   \
+        return launch_pass<P>("bwd_dq", prm, a.plan, 0, a.plan->t_pos, a.stream);                                   \
+    }
+    GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
+#undef GTA_CALL
+    return GTA_OK;
+}
+
 template <class T> gta_status run(const AttnArgs& a) {
     const Shape& sh = a.shape;
 #define GTA_CALL(LHc, Gc)                                                                            \
@@ -95,7 +154,7 @@ template <class T> gta_status run(const AttnArgs& a) {
                                (const char*)a.out, (const char*)a.dO, (char*)a.dQ, a.lse_in,         \
                                a.rowstat, a.partial, sh.row_bytes, a.scale * kLog2e, a.scale,        \
                                sh.heads};                                                            \
-        return launch_pass<P>("bwd_dst", prm, a.plan, 0, a.stream);                                  \
+        return launch_pass<P>("bwd_dst", prm, a.plan, 0, nullptr, a.stream);                                  \
     }
     GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
 #undef GTA_CALL
@@ -103,6 +162,14 @@ template <class T> gta_status run(const AttnArgs& a) {
 }
 
 }  // namespace
+
+gta_status launch_rowstat(const AttnArgs& a) {
+    return a.shape.elem_bytes == 4 ? run_rowstat<float>(a) : run_rowstat<bf16_tag>(a);
+}
+
+gta_status launch_bwd_dq(const AttnArgs& a) {
+    return a.shape.elem_bytes == 4 ? run_dq<float>(a) : run_dq<bf16_tag>(a);
+}
 
 gta_status launch_bwd_dst(const AttnArgs& a) {
     return a.shape.elem_bytes == 4 ? run<float>(a) : run<bf16_tag>(a);

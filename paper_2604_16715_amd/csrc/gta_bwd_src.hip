@@ -3,21 +3,26 @@
 //     dK_j = sum_{i : j in N(i)} scale * dZ_ij * q_i   (dK = dZ^T Q)
 // walked over the plan's transposed pattern so each source row is owned by one group of lanes
 // and summed in a fixed order (no atomics).  Per entry the weight a_ij and dZ_ij are recomputed
-// from q_i, dY_i and the (lse, delta) pair the destination-major pass left for row i.
+// from q_i, dY_i and the (lse, delta) pair of row i.  With STORE the pass also writes dZ_ij
+// (unscaled) to a float [nnz, heads] array in the order it walks (transposed order, so the writes
+// are contiguous); dQ = dZ K afterwards runs as a plain SpMM that gathers only K and finds each
+// entry's dZ through the plan's stored-position -> transposed-position map.
 #include "gta_kernels.h"
 
 namespace gta {
 namespace {
 
-template <class T, int LH_, int G_>
+template <class T, int LH_, int G_, bool STORE>
 struct BwdSrcPass {
     static constexpr int LH = LH_, G = G_, U = UnrollFor<G_>::value;
     static constexpr int NV = Elt<T>::NV;
+    static constexpr bool kUsesEntryId = STORE;
     static constexpr int N = 2 * NV;   // f = dK accumulator (unscaled), then dV accumulator
     struct Params {
         const char *Q, *dO, *K, *V;
         char *dK, *dV;
         const float2* rowstat;
+        float* dS;
         float* partial;
         int64_t stride;
         float qscale, scale;
@@ -27,10 +32,16 @@ struct BwdSrcPass {
     float f[N];
     uint4 qr[U], gr[U];
     float2 st[U];
+    int eids[U];
+    float* ds_out;
+    int n_heads, my_lig;
 
     __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) { k2[i] = 0.f; v[i] = 0.f; f[i] = 0.f; f[NV + i] = 0.f; }
+        ds_out = p.dS;
+        n_heads = p.heads;
+        my_lig = lig;
         if (active) {
             Elt<T>::unpack(load16(p.K, row, p.stride, lig), k2);
             Elt<T>::unpack(load16(p.V, row, p.stride, lig), v);
@@ -38,7 +49,8 @@ struct BwdSrcPass {
             for (int i = 0; i < NV; ++i) k2[i] *= p.qscale;
         }
     }
-    __device__ __forceinline__ void load(const Params& p, int u, int i, bool ok, int lig) {
+    __device__ __forceinline__ void load(const Params& p, int u, int i, int e, bool ok, int lig) {
+        eids[u] = e;
         qr[u] = make_uint4(0, 0, 0, 0);
         gr[u] = make_uint4(0, 0, 0, 0);
         st[u] = make_float2(0.f, 0.f);
@@ -61,6 +73,7 @@ struct BwdSrcPass {
             da = head_allreduce<LH>(da);
             const float a = ok[u] ? fast_exp2(s - st[u].x) : 0.f;
             const float dz = a * (da - st[u].y);
+            if (STORE && ok[u] && my_lig % LH == 0) ds_out[(int64_t)eids[u] * n_heads + my_lig / LH] = dz;
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 f[i] = fmaf(dz, q[i], f[i]);
@@ -81,15 +94,15 @@ struct BwdSrcPass {
     }
 };
 
-template <class T> gta_status run(const AttnArgs& a) {
+template <class T, bool STORE> gta_status run(const AttnArgs& a) {
     const Shape& sh = a.shape;
 #define GTA_CALL(LHc, Gc)                                                                         \
     {                                                                                             \
-        using P = BwdSrcPass<T, LHc, Gc>;                                                         \
+        using P = BwdSrcPass<T, LHc, Gc, STORE>;                                                  \
         typename P::Params prm{(const char*)a.Q, (const char*)a.dO, (const char*)a.K,             \
-                               (const char*)a.V, (char*)a.dK, (char*)a.dV, a.rowstat, a.partial,  \
-                               sh.row_bytes, a.scale * kLog2e, a.scale, sh.heads};                \
-        return launch_pass<P>("bwd_src", prm, a.plan, 1, a.stream);                               \
+                               (const char*)a.V, (char*)a.dK, (char*)a.dV, a.rowstat, a.dS,       \
+                               a.partial, sh.row_bytes, a.scale * kLog2e, a.scale, sh.heads};     \
+        return launch_pass<P>("bwd_src", prm, a.plan, 1, nullptr, a.stream);                               \
     }
     GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
 #undef GTA_CALL
@@ -99,7 +112,8 @@ template <class T> gta_status run(const AttnArgs& a) {
 }  // namespace
 
 gta_status launch_bwd_src(const AttnArgs& a) {
-    return a.shape.elem_bytes == 4 ? run<float>(a) : run<bf16_tag>(a);
+    if (a.dS) return a.shape.elem_bytes == 4 ? run<float, true>(a) : run<bf16_tag, true>(a);
+    return a.shape.elem_bytes == 4 ? run<float, false>(a) : run<bf16_tag, false>(a);
 }
 
 }  // namespace gta

@@ -11,6 +11,7 @@ template <class T, int LH_, int G_>
 struct FwdPass {
     static constexpr int LH = LH_, G = G_, U = UnrollFor<G_>::value;
     static constexpr int NV = Elt<T>::NV;
+    static constexpr bool kUsesEntryId = false;
     static constexpr int N = NV + 2;   // f = accumulator[NV], running max, running sum
     struct Params {
         const char *Q, *K, *V;
@@ -36,7 +37,7 @@ struct FwdPass {
             for (int i = 0; i < NV; ++i) q[i] *= p.qscale;
         }
     }
-    __device__ __forceinline__ void load(const Params& p, int u, int j, bool ok, int lig) {
+    __device__ __forceinline__ void load(const Params& p, int u, int j, int, bool ok, int lig) {
         kr[u] = make_uint4(0, 0, 0, 0);
         vr[u] = make_uint4(0, 0, 0, 0);
         if (ok) {
@@ -101,7 +102,7 @@ template <class T> gta_status run(const AttnArgs& a) {
         using P = FwdPass<T, LHc, Gc>;                                                                \
         typename P::Params prm{(const char*)a.Q, (const char*)a.K, (const char*)a.V, (char*)a.o_out,  \
                                a.lse_out, a.partial, sh.row_bytes, a.scale * kLog2e, sh.heads};       \
-        return launch_pass<P>("fwd", prm, a.plan, 0, a.stream);                                       \
+        return launch_pass<P>("fwd", prm, a.plan, 0, nullptr, a.stream);                                       \
     }
     GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
 #undef GTA_CALL

@@ -30,12 +30,14 @@ struct Side {
 struct gta_plan {
     int64_t n_dst = 0, n_src = 0, nnz = 0;
     int32_t pack_max_deg = 0, wave_max_deg = 0, hub_chunk = 0;
+    int64_t keep_dz_min_nnz = 262144;
     int device = 0;
     const int64_t* indptr = nullptr;
     const int32_t* indices = nullptr;
     int64_t* t_indptr = nullptr;   // device [n_src + 1]
     int32_t* t_indices = nullptr;  // device [nnz]
-    int32_t* t_eid = nullptr;      // device [nnz]
+    int32_t* t_eid = nullptr;      // device [nnz]: stored position of each transposed entry
+    int32_t* t_pos = nullptr;      // device [nnz]: inverse of t_eid (transposed position of each stored entry)
     gta::Side side[2];
 };
 
@@ -98,6 +100,7 @@ struct AttnArgs {
     float* lse_out;
     float2* rowstat;     // [n_dst, heads] (lse * log2(e), delta)
     float* partial;      // scratch for split rows
+    float* dS;           // [nnz, heads] softmax-backward values per stored entry, or null
     float scale;
     Shape shape;
     hipStream_t stream;
@@ -105,6 +108,8 @@ struct AttnArgs {
 
 gta_status launch_fwd(const AttnArgs& a);
 gta_status launch_bwd_dst(const AttnArgs& a);
-gta_status launch_bwd_src(const AttnArgs& a);
+gta_status launch_bwd_src(const AttnArgs& a);   // stores dS when a.dS is set
+gta_status launch_rowstat(const AttnArgs& a);   // (lse * log2 e, dY_i . Y_i) per (row, head)
+gta_status launch_bwd_dq(const AttnArgs& a);    // dQ = scale * dS K over the stored dS
 
 }  // namespace gta

@@ -92,25 +92,34 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 struct RowSet {
     const int64_t* ptr;    // row pointer of the pattern being walked
     const int32_t* idx;    // its column ids
+    const int32_t* eid;    // walk position -> index into per-entry arrays (null: identity)
     const int32_t* rows;   // plan order of the rows
     int64_t begin, end;    // this launch covers rows[begin .. end)
 };
 struct ChunkSet {
     const int64_t* ptr;
     const int32_t* idx;
+    const int32_t* eid;
     const int4* chunks;          // (row, begin, end, chunks of row)
     const int32_t* chunk_ptr;    // first chunk of the r-th chunked row
     const int32_t* rows;
     int64_t n_chunks, n_hub;
 };
 
+// position of entry `pos` in the caller's per-entry arrays, for passes that read or write them
+template <class Pass>
+__device__ __forceinline__ int entry_id(const int32_t* eid, int pos, bool valid) {
+    if (!Pass::kUsesEntryId || !valid) return 0;
+    return eid ? eid[pos] : pos;
+}
+
 // One batch of up to 64 consecutive entries held one per lane (slot t lives in lane lane_base+t).
 // The calling group takes slots first, first+stride, ...  The trip count depends only on nb, so
 // every lane that shares the batch stays in the loop together: a cross-lane read must never
 // name a lane that has already left it.
 template <class Pass>
-__device__ __forceinline__ void run_batch(Pass& ps, const typename Pass::Params& prm, int my_idx, int nb,
-                                          int lane_base, int first, int stride, int lig) {
+__device__ __forceinline__ void run_batch(Pass& ps, const typename Pass::Params& prm, int my_idx, int my_eid,
+                                          int nb, int lane_base, int first, int stride, int lig) {
     constexpr int U = Pass::U;
     for (int t0 = 0; t0 < nb; t0 += U * stride) {
         bool ok[U];
@@ -119,7 +128,8 @@ __device__ __forceinline__ void run_batch(Pass& ps, const typename Pass::Params&
             const int t = t0 + u * stride + first;
             ok[u] = t < nb;
             const int j = __shfl(my_idx, (lane_base + t) & 63);
-            ps.load(prm, u, j, ok[u], lig);
+            const int e = Pass::kUsesEntryId ? __shfl(my_eid, (lane_base + t) & 63) : 0;
+            ps.load(prm, u, j, e, ok[u], lig);
         }
         ps.compute(ok);
     }
@@ -157,7 +167,8 @@ __device__ __forceinline__ void body_packed(const typename Pass::Params& prm, co
     for (int bb = b; bb < e; bb += G) {
         const int nb = min(G, e - bb);
         const int my = lig < nb ? rs.idx[bb + lig] : 0;
-        run_batch(ps, prm, my, nb, g * G, 0, 1, lig);
+        const int my_e = entry_id<Pass>(rs.eid, bb + lig, lig < nb);
+        run_batch(ps, prm, my, my_e, nb, g * G, 0, 1, lig);
     }
     if (active) Pass::finish(prm, row, lig, ps.f);
 }
@@ -175,7 +186,8 @@ __device__ __forceinline__ void body_wave(const typename Pass::Params& prm, cons
     for (int bb = b; bb < e; bb += 64) {
         const int nb = min(64, e - bb);
         const int my = lane < nb ? rs.idx[bb + lane] : 0;
-        run_batch(ps, prm, my, nb, 0, g, W, lig);
+        const int my_e = entry_id<Pass>(rs.eid, bb + lane, lane < nb);
+        run_batch(ps, prm, my, my_e, nb, 0, g, W, lig);
     }
     wave_merge<Pass>(ps.f);
     if (g == 0) Pass::finish(prm, row, lig, ps.f);
@@ -194,7 +206,8 @@ __device__ __forceinline__ void body_chunk(const typename Pass::Params& prm, con
     for (int bb = cb + 64 * w; bb < ce; bb += 64 * kWavesPerBlock) {
         const int nb = min(64, ce - bb);
         const int my = lane < nb ? cs.idx[bb + lane] : 0;
-        run_batch(ps, prm, my, nb, 0, g, W, lig);
+        const int my_e = entry_id<Pass>(cs.eid, bb + lane, lane < nb);
+        run_batch(ps, prm, my, my_e, nb, 0, g, W, lig);
     }
     wave_merge<Pass>(ps.f);
     if (w > 0 && g == 0) {
@@ -271,17 +284,19 @@ __global__ void __launch_bounds__(kBlockThreads) k_merge(typename Pass::Params p
 
 // ---------------------------------------------------------------- launching a pass
 // One launch covers every row of the side (plus the small merge launch when hub rows exist).
+// entry_map translates a position in the walked pattern into an index of the caller's per-entry
+// arrays (null: the position itself); only passes with kUsesEntryId look at it.
 // With split timing requested each schedule gets its own launch so it can be timed by itself.
 template <class Pass>
 gta_status launch_pass(const char* name, const typename Pass::Params& prm, const gta_plan* plan, int side,
-                       hipStream_t st) {
+                       const int32_t* entry_map, hipStream_t st) {
     constexpr int W = 64 / Pass::G;
     const Side& sd = plan->side[side];
     const Split sp = make_split(plan, side, Pass::G);
     char label[40];
-    ChunkSet cs{sd.ptr, sd.idx, sd.chunks, sd.chunk_ptr, sd.bin_rows, sd.n_chunks, sd.n_hub};
-    const RowSet wave{sd.ptr, sd.idx, sd.bin_rows, sp.wave_begin, sp.wave_end};
-    const RowSet packed{sd.ptr, sd.idx, sd.bin_rows, sp.pack_begin, sp.pack_end};
+    ChunkSet cs{sd.ptr, sd.idx, entry_map, sd.chunks, sd.chunk_ptr, sd.bin_rows, sd.n_chunks, sd.n_hub};
+    const RowSet wave{sd.ptr, sd.idx, entry_map, sd.bin_rows, sp.wave_begin, sp.wave_end};
+    const RowSet packed{sd.ptr, sd.idx, entry_map, sd.bin_rows, sp.pack_begin, sp.pack_end};
     const int64_t wave_blocks = (sp.wave_end - sp.wave_begin + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t per_block = kWavesPerBlock * W;
     const int64_t pack_blocks = (sp.pack_end - sp.pack_begin + per_block - 1) / per_block;

@@ -1,0 +1,293 @@
+// The paper's operators as standalone kernels (Section 2.2 counts them: forward 1 SDDMM + softmax
+// + 1 SpMM; backward 3 SpMM + 1 SDDMM), with the per-entry matrices Z, U, dU, dZ stored as
+// float [nnz, heads].  They reuse the row schedules of the fused passes.  The fused path never
+// calls them; they exist so the unfused decomposition can be run and timed operator by operator.
+#include "gta_kernels.h"
+#include "gta_spmm_pass.h"
+
+#include <type_traits>
+
+namespace gta {
+namespace {
+
+// ---------------------------------------------------------------- SDDMM: Z[e,h] = x_i . y_j
+template <class T, int LH_, int G_>
+struct SddmmPass {
+    static constexpr int LH = LH_, G = G_, U = UnrollFor<G_>::value;
+    static constexpr int NV = Elt<T>::NV;
+    static constexpr bool kUsesEntryId = true;
+    static constexpr int N = 1;   // nothing is accumulated across entries
+    struct Params {
+        const char *X, *Y;
+        float* Z;
+        float* partial;
+        int64_t stride;
+        int heads;
+    };
+    float x[NV];
+    float f[N];
+    uint4 yr[U];
+    int eids[U];
+
+    __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) x[i] = 0.f;
+        f[0] = 0.f;
+        zp = p.Z;
+        heads = p.heads;
+        my_lig = lig;
+        if (active) Elt<T>::unpack(load16(p.X, row, p.stride, lig), x);
+    }
+    __device__ __forceinline__ void load(const Params& p, int u, int j, int e, bool ok, int lig) {
+        yr[u] = make_uint4(0, 0, 0, 0);
+        eids[u] = e;
+        if (ok) yr[u] = load16(p.Y, j, p.stride, lig);
+    }
+    __device__ __forceinline__ void compute(const bool (&ok)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float y[NV];
+            Elt<T>::unpack(yr[u], y);
+            float d = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) d = fmaf(x[i], y[i], d);
+            d = head_allreduce<LH>(d);
+            if (ok[u] && my_lig % LH == 0) zp[(int64_t)eids[u] * heads + my_lig / LH] = d;
+        }
+    }
+    static __device__ __forceinline__ void combine(float (&)[N], const float (&)[N]) {}
+    static __device__ __forceinline__ void finish(const Params&, int, int, const float (&)[N]) {}
+    float* zp;
+    int heads, my_lig;
+};
+
+// ---------------------------------------------------------------- edge softmax over float [nnz, H]
+// A team of TEAM threads owns one row; thread t of the team walks the row's deg*H contiguous
+// values with stride TEAM, so it always sees head t % H (TEAM is a multiple of H).
+template <int TEAM> struct TeamReduce {
+    // combines (m, l) pairs of an online softmax over the team members that share t % H
+    static __device__ __forceinline__ void softmax(float& m, float& l, int H, float* lds) {
+        for (int off = H; off < 64; off <<= 1) {
+            const float om = __shfl_xor(m, off), ol = __shfl_xor(l, off);
+            const float mn = fmaxf(m, om);
+            l = l * fast_exp2(m - mn) + ol * fast_exp2(om - mn);
+            m = mn;
+        }
+        if (TEAM > 64) {   // wavefronts of a workgroup: through LDS, in wavefront order
+            const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+            __syncthreads();
+            if (lane < H) { lds[(w * 64 + lane) * 2] = m; lds[(w * 64 + lane) * 2 + 1] = l; }
+            __syncthreads();
+            float am = kNegBig, al = 0.f;
+            for (int k = 0; k < TEAM / 64; ++k) {
+                const float om = lds[(k * 64 + lane % H) * 2], ol = lds[(k * 64 + lane % H) * 2 + 1];
+                const float mn = fmaxf(am, om);
+                al = al * fast_exp2(am - mn) + ol * fast_exp2(om - mn);
+                am = mn;
+            }
+            m = am;
+            l = al;
+        }
+    }
+    static __device__ __forceinline__ float sum(float v, int H, float* lds) {
+        for (int off = H; off < 64; off <<= 1) v += __shfl_xor(v, off);
+        if (TEAM > 64) {
+            const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+            __syncthreads();
+            if (lane < H) lds[w * 64 + lane] = v;
+            __syncthreads();
+            float acc = 0.f;
+            for (int k = 0; k < TEAM / 64; ++k) acc += lds[k * 64 + lane % H];
+            v = acc;
+        }
+        return v;
+    }
+};
+
+template <int TEAM>
+__global__ void __launch_bounds__(kBlockThreads)
+k_edge_softmax(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64_t row_end, int H,
+               float scale2, const float* Z, float* U, float* lse) {
+    __shared__ float lds[kBlockThreads * 2];
+    const int64_t team = ((int64_t)blockIdx.x * kBlockThreads + threadIdx.x) / TEAM;
+    const int t = threadIdx.x % TEAM;
+    const int64_t r = row_begin + team;
+    const bool active = r < row_end;   // uniform over the team (and over the block when TEAM == block)
+    int64_t b = 0, e = 0;
+    int row = 0;
+    if (active) {
+        row = rows[r];
+        b = ptr[row] * H;
+        e = ptr[row + 1] * H;
+    }
+    float m = kNegBig, l = 0.f;
+    for (int64_t x = b + t; x < e; x += TEAM) {
+        const float s = Z[x] * scale2;
+        const float mn = fmaxf(m, s);
+        l = l * fast_exp2(m - mn) + fast_exp2(s - mn);
+        m = mn;
+    }
+    TeamReduce<TEAM>::softmax(m, l, H, lds);
+    const float lse2 = m + fast_log2(l);
+    for (int64_t x = b + t; x < e; x += TEAM) U[x] = fast_exp2(Z[x] * scale2 - lse2);
+    if (active && lse && t < H) lse[(int64_t)row * H + t] = e > b ? lse2 * kLn2 : -INFINITY;
+}
+
+template <int TEAM>
+__global__ void __launch_bounds__(kBlockThreads)
+k_edge_softmax_bwd(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64_t row_end, int H,
+                   float scale, const float* U, const float* dU, float* dZ) {
+    __shared__ float lds[kBlockThreads * 2];
+    const int64_t team = ((int64_t)blockIdx.x * kBlockThreads + threadIdx.x) / TEAM;
+    const int t = threadIdx.x % TEAM;
+    const int64_t r = row_begin + team;
+    int64_t b = 0, e = 0;
+    if (r < row_end) {
+        const int row = rows[r];
+        b = ptr[row] * H;
+        e = ptr[row + 1] * H;
+    }
+    float dot = 0.f;
+    for (int64_t x = b + t; x < e; x += TEAM) dot = fmaf(U[x], dU[x], dot);
+    dot = TeamReduce<TEAM>::sum(dot, H, lds);
+    for (int64_t x = b + t; x < e; x += TEAM) dZ[x] = scale * U[x] * (dU[x] - dot);
+}
+
+template <class T> gta_status run_sddmm(const gta_plan* plan, const Shape& sh, const void* X, const void* Y,
+                                        float* Z, float* partial, hipStream_t st) {
+#define GTA_CALL(LHc, Gc)                                                                        \
+    {                                                                                            \
+        using P = SddmmPass<T, LHc, Gc>;                                                         \
+        typename P::Params prm{(const char*)X, (const char*)Y, Z, partial, sh.row_bytes, sh.heads}; \
+        return launch_pass<P>("sddmm", prm, plan, 0, nullptr, st);                                        \
+    }
+    GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
+#undef GTA_CALL
+    return GTA_OK;
+}
+
+template <class T> gta_status run_spmm(const gta_plan* plan, int side, const Shape& sh, const float* W,
+                                       const void* X, void* Y, float* partial, hipStream_t st) {
+#define GTA_CALL(LHc, Gc)                                                                        \
+    {                                                                                            \
+        using P = SpmmPass<T, LHc, Gc>;                                                          \
+        typename P::Params prm{W, (const char*)X, (char*)Y, partial, sh.row_bytes, 1.0f, sh.heads};    \
+        return launch_pass<P>(side ? "spmm_t" : "spmm", prm, plan, side, side ? plan->t_eid : nullptr, st);                    \
+    }
+    GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
+#undef GTA_CALL
+    return GTA_OK;
+}
+
+bool head_count_ok(int heads) { return heads >= 1 && heads <= 64 && (heads & (heads - 1)) == 0; }
+
+// scratch holds the per-chunk partial results of the row schedules (same sizing as the fused path)
+gta_status partial_area(const gta_plan* plan, const Shape& sh, void* scratch, size_t scratch_bytes, float** out) {
+    const size_t need = gta_attn_scratch_bytes_min(plan, sh.heads, sh.head_dim, sh.elem_bytes == 4 ? GTA_F32 : GTA_BF16);
+    if (!scratch) return fail(GTA_ERR_INVALID_ARG, "scratch is null");
+    if (((uintptr_t)scratch & 255) != 0) return fail(GTA_ERR_INVALID_ARG, "scratch must be 256-byte aligned");
+    if (scratch_bytes < need) return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
+    *out = static_cast<float*>(scratch);
+    return GTA_OK;
+}
+
+gta_status check_graph(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, int64_t n_dst,
+                       int64_t n_src) {
+    if (!plan) return fail(GTA_ERR_INVALID_ARG, "plan is null");
+    if (indptr != plan->indptr || (indices && indices != plan->indices))
+        return fail(GTA_ERR_INVALID_ARG, "indptr/indices differ from the arrays the plan was built for");
+    if (n_dst != plan->n_dst || (n_src >= 0 && n_src != plan->n_src))
+        return fail(GTA_ERR_INVALID_ARG, "n_dst/n_src differ from the plan's");
+    return GTA_OK;
+}
+
+}  // namespace
+}  // namespace gta
+
+using namespace gta;
+
+extern "C" GTA_API gta_status gta_sddmm(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                        const void* X, const void* Y, float* Z, int64_t n_dst, int64_t n_src,
+                                        int heads, int head_dim, gta_dtype dtype, void* scratch,
+                                        size_t scratch_bytes, void* stream) {
+    gta_status rc = check_graph(plan, indptr, indices, n_dst, n_src);
+    if (rc != GTA_OK) return rc;
+    Shape sh;
+    if ((rc = make_shape(heads, head_dim, dtype, &sh)) != GTA_OK) return rc;
+    if ((n_dst > 0 && !X) || (n_src > 0 && !Y) || (plan->nnz > 0 && !Z)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15)) return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    float* partial;
+    if ((rc = partial_area(plan, sh, scratch, scratch_bytes, &partial)) != GTA_OK) return rc;
+    if (n_dst == 0) return GTA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return sh.elem_bytes == 4 ? run_sddmm<float>(plan, sh, X, Y, Z, partial, st)
+                              : run_sddmm<bf16_tag>(plan, sh, X, Y, Z, partial, st);
+}
+
+extern "C" GTA_API gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                       const float* W, const void* X, void* Y, int64_t n_dst, int64_t n_src,
+                                       int heads, int head_dim, gta_dtype dtype, int transposed, void* scratch,
+                                       size_t scratch_bytes, void* stream) {
+    gta_status rc = check_graph(plan, indptr, indices, n_dst, n_src);
+    if (rc != GTA_OK) return rc;
+    Shape sh;
+    if ((rc = make_shape(heads, head_dim, dtype, &sh)) != GTA_OK) return rc;
+    const int64_t rows_out = transposed ? n_src : n_dst, rows_in = transposed ? n_dst : n_src;
+    if ((rows_in > 0 && !X) || (rows_out > 0 && !Y) || (plan->nnz > 0 && !W)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15)) return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    float* partial;
+    if ((rc = partial_area(plan, sh, scratch, scratch_bytes, &partial)) != GTA_OK) return rc;
+    if (rows_out == 0) return GTA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int side = transposed ? 1 : 0;
+    return sh.elem_bytes == 4 ? run_spmm<float>(plan, side, sh, W, X, Y, partial, st)
+                              : run_spmm<bf16_tag>(plan, side, sh, W, X, Y, partial, st);
+}
+
+namespace {
+template <class Launch> gta_status softmax_launches(const gta_plan* plan, const char* name, Launch launch) {
+    const Side& sd = plan->side[0];
+    // rows above wave_max_deg: one workgroup each; the rest: one wavefront each
+    if (sd.n_chunked > 0) launch(std::integral_constant<int, kBlockThreads>(), (int64_t)0, sd.n_chunked, sd.n_chunked);
+    const int64_t rest = sd.n_rows - sd.n_chunked;
+    if (rest > 0)
+        launch(std::integral_constant<int, 64>(), sd.n_chunked, sd.n_rows, (rest + kWavesPerBlock - 1) / kWavesPerBlock);
+    (void)name;
+    GTA_HIP_TRY(hipGetLastError());
+    return GTA_OK;
+}
+}  // namespace
+
+extern "C" GTA_API gta_status gta_edge_softmax(const gta_plan* plan, const int64_t* indptr, const float* Z,
+                                               float* U, float* lse, int64_t n_dst, int heads, float scale,
+                                               void* stream) {
+    gta_status rc = check_graph(plan, indptr, nullptr, n_dst, -1);
+    if (rc != GTA_OK) return rc;
+    if (!head_count_ok(heads)) return fail(GTA_ERR_UNSUPPORTED, "heads must be a power of two <= 64");
+    if (!(scale > 0.f)) return fail(GTA_ERR_INVALID_ARG, "scale must be positive");
+    if (plan->nnz > 0 && (!Z || !U)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Side& sd = plan->side[0];
+    LaunchTimer t("edge_softmax", sd.n_rows, plan->nnz, st);
+    return softmax_launches(plan, "edge_softmax", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
+        hipLaunchKernelGGL(k_edge_softmax<decltype(team)::value>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st,
+                           sd.ptr, sd.bin_rows, rb, re, heads, scale * kLog2e, Z, U, lse);
+    });
+}
+
+extern "C" GTA_API gta_status gta_edge_softmax_bwd(const gta_plan* plan, const int64_t* indptr, const float* U,
+                                                   const float* dU, float* dZ, int64_t n_dst, int heads,
+                                                   float scale, void* stream) {
+    gta_status rc = check_graph(plan, indptr, nullptr, n_dst, -1);
+    if (rc != GTA_OK) return rc;
+    if (!head_count_ok(heads)) return fail(GTA_ERR_UNSUPPORTED, "heads must be a power of two <= 64");
+    if (!(scale > 0.f)) return fail(GTA_ERR_INVALID_ARG, "scale must be positive");
+    if (plan->nnz > 0 && (!U || !dU || !dZ)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Side& sd = plan->side[0];
+    LaunchTimer t("edge_softmax_bwd", sd.n_rows, plan->nnz, st);
+    return softmax_launches(plan, "edge_softmax_bwd", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
+        hipLaunchKernelGGL(k_edge_softmax_bwd<decltype(team)::value>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st,
+                           sd.ptr, sd.bin_rows, rb, re, heads, scale, U, dU, dZ);
+    });
+}

@@ -24,6 +24,11 @@ __global__ void k_iota(int32_t* v, int64_t n) {
     if (i < n) v[i] = (int32_t)i;
 }
 
+__global__ void k_invert(const int32_t* perm, int32_t* inv, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) inv[perm[i]] = (int32_t)i;
+}
+
 __global__ void k_copy_keys(const int32_t* in, uint32_t* out, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = (uint32_t)in[i];
@@ -241,13 +246,14 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline dim3 grid_for(int64_t n, int threads) { return dim3((unsigned)std::max<int64_t>(1, ceil_div(n, threads))); }
 
-struct Opts { int pack, wave, chunk, validate; };
+struct Opts { int pack, wave, chunk, validate; int64_t keep_dz; };
 
 bool resolve_opts(const gta_plan_opts* o, Opts* r) {
     r->pack = o && o->pack_max_deg > 0 ? o->pack_max_deg : 0;
     r->wave = o && o->wave_max_deg > 0 ? o->wave_max_deg : 512;
     r->chunk = o && o->hub_chunk > 0 ? o->hub_chunk : 2048;
     r->validate = o ? o->validate : 0;
+    r->keep_dz = !o || o->keep_dz_min_nnz == 0 ? 262144 : (o->keep_dz_min_nnz < 0 ? INT64_MAX : o->keep_dz_min_nnz);
     auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     if (!pow2(r->wave) || !pow2(r->chunk) || r->chunk < r->wave) return false;
     if (r->pack != 0 && (!pow2(r->pack) || r->pack > r->wave)) return false;
@@ -255,7 +261,7 @@ bool resolve_opts(const gta_plan_opts* o, Opts* r) {
 }
 
 struct Layout {
-    size_t bin_rows[2], chunk_ptr[2], chunks[2], t_indptr, t_indices, t_eid;
+    size_t bin_rows[2], chunk_ptr[2], chunks[2], t_indptr, t_indices, t_eid, t_pos;
     size_t key_a, key_b, val_a, val_b, hist, tile_sum, stats, flag, total;
     int64_t max_chunked[2], max_chunks[2], sort_cap, hist_cap, tile_cap;
 };
@@ -274,6 +280,7 @@ void make_layout(int64_t n_dst, int64_t n_src, int64_t nnz, const Opts& o, Layou
     L->t_indptr = take(sizeof(int64_t) * (size_t)(n_src + 1));
     L->t_indices = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, nnz));
     L->t_eid = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, nnz));
+    L->t_pos = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, nnz));
     L->sort_cap = std::max<int64_t>(1, std::max(nnz, std::max(n_dst, n_src)));
     L->key_a = take(4 * (size_t)L->sort_cap);
     L->key_b = take(4 * (size_t)L->sort_cap);
@@ -437,6 +444,7 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
     struct Guard { gta_plan* p; ~Guard() { delete p; } } guard{p};
     p->n_dst = n_dst; p->n_src = n_src; p->nnz = nnz;
     p->pack_max_deg = o.pack; p->wave_max_deg = o.wave; p->hub_chunk = o.chunk;
+    p->keep_dz_min_nnz = o.keep_dz;
     p->indptr = indptr; p->indices = indices;
     GTA_HIP_TRY(hipGetDevice(&p->device));
 
@@ -460,6 +468,7 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
     p->t_indptr = b.at<int64_t>(b.L.t_indptr);
     p->t_indices = b.at<int32_t>(b.L.t_indices);
     p->t_eid = b.at<int32_t>(b.L.t_eid);
+    p->t_pos = b.at<int32_t>(b.L.t_pos);
     {
         uint32_t* ka = b.at<uint32_t>(b.L.key_a);
         int32_t* va = b.at<int32_t>(b.L.val_a);
@@ -478,6 +487,7 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
             GTA_HIP_TRY(hipMemcpyAsync(p->t_eid, vs, sizeof(int32_t) * (size_t)nnz, hipMemcpyDeviceToDevice, b.st));
             hipLaunchKernelGGL(k_row_of_entry, grid_for(nnz, 256), dim3(256), 0, b.st, indptr, n_dst,
                                p->t_eid, nnz, p->t_indices);
+            hipLaunchKernelGGL(k_invert, grid_for(nnz, 256), dim3(256), 0, b.st, p->t_eid, p->t_pos, nnz);
         }
         GTA_HIP_TRY(hipGetLastError());
     }

@@ -80,17 +80,20 @@ class Problem:
                                self.f64("dO"), scale)
 
 
-def run_gpu(p: Problem, scale=0.0, plan_kwargs=None, backward=True):
-    """Plan + forward (+ backward) through the C ABI.  Returns dict of float64 host arrays + plan."""
+def run_gpu(p: Problem, scale=0.0, plan_kwargs=None, backward=True, lean_scratch=False):
+    """Plan + forward (+ backward) through the C ABI.  Returns dict of float64 host arrays + plan.
+    lean_scratch selects the backward form that keeps nothing per stored entry."""
     import paper_2604_16715_amd as gta
     indptr = torch.from_numpy(p.indptr).cuda()
     indices = torch.from_numpy(p.indices).cuda()
-    plan = gta.gta_plan_create(indptr, indices, p.n_src, validate=True, **(plan_kwargs or {}))
+    kw = dict(keep_dz_min_nnz=1)   # small test graphs must still run the dZ-keeping backward
+    kw.update(plan_kwargs or {})
+    plan = gta.gta_plan_create(indptr, indices, p.n_src, validate=True, **kw)
     Q, K, V, dO = (to_torch(getattr(p, k)) for k in ("Q", "K", "V", "dO"))
     out, lse = gta.gta_attn_fwd(plan, Q, K, V, scale)
     res = dict(plan=plan, out=to_f64(out), lse=to_f64(lse), raw_out=out, raw_lse=lse)
     if backward:
-        dQ, dK, dV = gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO, scale)
+        dQ, dK, dV = gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO, scale, lean_scratch=lean_scratch)
         res.update(dQ=to_f64(dQ), dK=to_f64(dK), dV=to_f64(dV), raw=(dQ, dK, dV))
     torch.cuda.synchronize()
     return res

@@ -40,11 +40,11 @@ def test_workspace_query_is_host_only(lib):
     assert lib.gta_plan_workspace_bytes(1000, 1500, 20000, None) > 20000 * 8
     assert lib.gta_plan_workspace_bytes(-1, 10, 10, None) == 0
     assert lib.gta_plan_workspace_bytes(10, 10, 1 << 31, None) == 0
-    bad = _PlanOpts(0, 48, 0, 0)         # not a power of two
+    bad = _PlanOpts(0, 48, 0, 0, 0)         # not a power of two
     assert lib.gta_plan_workspace_bytes(10, 10, 10, ctypes.byref(bad)) == 0
-    bad = _PlanOpts(0, 512, 256, 0)      # hub_chunk < wave_max_deg
+    bad = _PlanOpts(0, 512, 256, 0, 0)      # hub_chunk < wave_max_deg
     assert lib.gta_plan_workspace_bytes(10, 10, 10, ctypes.byref(bad)) == 0
-    small = _PlanOpts(0, 4, 8, 0)
+    small = _PlanOpts(0, 4, 8, 0, 0)
     assert lib.gta_plan_workspace_bytes(10, 10, 100, ctypes.byref(small)) > 0
 
 

@@ -13,20 +13,22 @@ def check(p: Problem, scale=0.0, plan_kwargs=None, tag=""):
     print(f"attn case {tag} n_dst={p.n_dst} n_src={p.n_src} nnz={int(p.indptr[-1])} "
           f"shape={p.Q.shape[1:]} dtype={p.dtype} plan={plan_kwargs}", flush=True)
     tol = TOL[p.dtype]
-    res = run_gpu(p, scale, plan_kwargs)
     o_scale = None if scale <= 0 else scale
     out, lse = p.oracle_forward(o_scale)
     dQ, dK, dV = p.oracle_backward(o_scale)
-    assert_close("out", res["out"], out, tol)
-    assert_lse_close(res["lse"], lse, tol)
     empty = np.diff(p.indptr) == 0
-    assert np.all(res["out"][empty] == 0.0) and np.all(res["dQ"][empty] == 0.0)
-    assert_close("dQ", res["dQ"], dQ, tol)
-    assert_close("dK", res["dK"], dK, tol)
-    assert_close("dV", res["dV"], dV, tol)
     unused = np.ones(p.n_src, dtype=bool)
     unused[p.indices] = False
-    assert np.all(res["dK"][unused] == 0.0) and np.all(res["dV"][unused] == 0.0)
+    # both backward forms: dZ kept per stored entry (recommended scratch) and nothing kept (minimum scratch)
+    for lean in (False, True):
+        res = run_gpu(p, scale, plan_kwargs, lean_scratch=lean)
+        assert_close("out", res["out"], out, tol)
+        assert_lse_close(res["lse"], lse, tol)
+        assert np.all(res["out"][empty] == 0.0) and np.all(res["dQ"][empty] == 0.0)
+        assert_close("dQ", res["dQ"], dQ, tol)
+        assert_close("dK", res["dK"], dK, tol)
+        assert_close("dV", res["dV"], dV, tol)
+        assert np.all(res["dK"][unused] == 0.0) and np.all(res["dV"][unused] == 0.0)
     return res
 
 
@@ -91,10 +93,11 @@ def test_bitwise_reproducible():
     w = gen.workload("mid", 8)
     p = Problem.from_workload(w)
     kw = dict(wave_max_deg=16, hub_chunk=64)
-    a = run_gpu(p, plan_kwargs=kw)
-    b = run_gpu(p, plan_kwargs=kw)
-    for k in ("out", "lse", "dQ", "dK", "dV"):
-        assert np.array_equal(a[k], b[k], equal_nan=True), k
+    for lean in (False, True):
+        a = run_gpu(p, plan_kwargs=kw, lean_scratch=lean)
+        b = run_gpu(p, plan_kwargs=kw, lean_scratch=lean)
+        for k in ("out", "lse", "dQ", "dK", "dV"):
+            assert np.array_equal(a[k], b[k], equal_nan=True), k
 
 
 def test_unsupported_shapes_are_reported():
