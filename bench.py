@@ -109,14 +109,28 @@ def time_unfused(gta, torch, plan, Q, K, V, dO, w, steps, log) -> dict:
     torch.cuda.synchronize()
     recs = gta.gta_profile_read(reset=True)
     gta.gta_profile_enable(0)
+    # algorithmic bytes per call: one row gather per entry plus the per-entry arrays, streams once
+    R = w.heads * w.head_dim * (4 if w.dtype == "f32" else 2)
+    op_bytes = {
+        "sddmm": E * (R + 4 + 4 * H) + w.n_dst * (R + 8),                 # gather + index + Z write | X row
+        "spmm": E * (R + 4 + 4 * H) + w.n_dst * (R + 8),                  # gather + index + W read | Y row
+        "spmm_t": E * (R + 8 + 4 * H) + w.n_src * (R + 8),                # + stored position of the entry
+        "edge_softmax": E * 12 * H + w.n_dst * (4 * H + 8),               # Z read twice, U write | lse
+        "edge_softmax_bwd": E * 20 * H + w.n_dst * 8,                     # U, dU read twice, dZ write
+    }
     per_op: dict = {}
     for r in recs:
-        per_op[r["name"]] = per_op.get(r["name"], 0.0) + r["ms"] / steps
-    for k, v in per_op.items():
-        log(f"  unfused {k:20s} {v:9.3f} ms per step")
-    return {"ms_per_step": ms, "edges_per_s": E / (ms * 1e-3),
-            "op_ms_per_step": {k: round(v, 4) for k, v in per_op.items()},
-            "note": "per step: 2 sddmm, 2 spmm, 2 spmm_t, 1 edge_softmax, 1 edge_softmax_bwd launches"}
+        k = per_op.setdefault(r["name"], {"ms": 0.0, "calls": 0})
+        k["ms"] += r["ms"]
+        k["calls"] += 1
+    ops = {}
+    for name, k in per_op.items():
+        avg = k["ms"] / k["calls"]
+        gbs = op_bytes[name] / (avg * 1e-3) / 1e9 if name in op_bytes else 0.0
+        ops[name] = {"avg_ms": round(avg, 4), "calls_per_step": k["calls"] // steps, "gbs": round(gbs, 1)}
+        log(f"  unfused {name:20s} {avg:9.3f} ms per call x{k['calls'] // steps}  {gbs:8.1f} GB/s")
+    return {"ms_per_step": ms, "edges_per_s": E / (ms * 1e-3), "ops": ops,
+            "edge_array_bytes": 4 * E * H * 4}
 
 
 def main() -> int:

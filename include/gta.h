@@ -165,6 +165,31 @@ gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* 
                     const void* X, void* Y, int64_t n_dst, int64_t n_src, int heads, int head_dim,
                     gta_dtype dtype, int transposed, void* scratch, size_t scratch_bytes, void* stream);
 
+/* ---- Layout transforms of GP-A2A (Section 3.2, Algorithm 2: [(N/p),h,d'] <-> [N,(h/p),d']).
+ * gta_head_split regroups X [n_rows, heads, head_dim] into `parts` contiguous blocks
+ * S [parts][n_rows, heads/parts, head_dim] (block r is what GPU r receives from this GPU);
+ * gta_head_merge is the inverse.  heads must be divisible by parts and a head block must be a
+ * multiple of 16 bytes.  The exchange itself (an all-to-all) is not part of this library.       */
+gta_status gta_head_split(const void* X, void* S, int64_t n_rows, int heads, int head_dim,
+                          gta_dtype dtype, int parts, void* stream);
+gta_status gta_head_merge(const void* S, void* X, int64_t n_rows, int heads, int head_dim,
+                          gta_dtype dtype, int parts, void* stream);
+
+/* ---- Automatic Graph Parallelism (Section 4.3, Algorithm 3).  Host arithmetic only; all pointers
+ * are HOST pointers.  With k = t_iter(1) / N, every measured coefficient beta_c(i) (seconds per
+ * node for strategy c on i GPUs, 2 <= i <= max_gpus) gives the term i * beta / (i - 1); the entry
+ * with the smallest term that does not exceed k is selected (ties: first in table order).
+ * *strategy = its strategy id and *gpus = i, or (-1, 1) when no entry qualifies (stay on one
+ * GPU).  est_t_iter (may be NULL) receives t_iter(1)/i + beta * N for the selection (Eq. 7 with
+ * alpha(i) = alpha(1)/i).  This build runs on one GPU, so the coefficients must come from elsewhere. */
+typedef struct {
+    int32_t strategy; /* caller-defined id, e.g. 0 = GP-AG, 1 = GP-A2A */
+    int32_t gpus;     /* i                                              */
+    double beta;      /* beta_c(i), seconds per node                    */
+} gta_agp_sample;
+gta_status gta_agp_select(double t_iter1_seconds, int64_t n_nodes, const gta_agp_sample* samples,
+                          int n_samples, int max_gpus, int* strategy, int* gpus, double* est_t_iter);
+
 /* Per-launch timing for benchmarks.  While enabled (on = 1), every kernel launch of
  * gta_attn_fwd/bwd is bracketed by HIP events on the call's stream.  on = 2 additionally launches
  * the three row schedules of a pass separately (instead of in one grid) so each is timed alone.  gta_profile_read synchronises those events and

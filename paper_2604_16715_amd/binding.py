@@ -31,6 +31,10 @@ class _PlanInfo(Structure):
                 ("n_chunked", c_int64 * 2), ("n_hub", c_int64 * 2), ("n_chunks", c_int64 * 2)]
 
 
+class _AgpSample(Structure):
+    _fields_ = [("strategy", c_int32), ("gpus", c_int32), ("beta", ctypes.c_double)]
+
+
 class _LaunchRecord(Structure):
     _fields_ = [("name", c_char * 40), ("ms", c_float), ("rows", c_int64), ("entries", c_int64)]
 
@@ -82,6 +86,12 @@ def load_library():
     lib.gta_spmm.restype = c_int
     lib.gta_spmm.argtypes = [vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int, c_int, vp,
                              c_size_t, vp]
+    for fn in (lib.gta_head_split, lib.gta_head_merge):
+        fn.restype = c_int
+        fn.argtypes = [vp, vp, c_int64, c_int, c_int, c_int, c_int, vp]
+    lib.gta_agp_select.restype = c_int
+    lib.gta_agp_select.argtypes = [ctypes.c_double, c_int64, POINTER(_AgpSample), c_int, c_int, POINTER(c_int),
+                                   POINTER(c_int), POINTER(ctypes.c_double)]
     lib.gta_profile_enable.restype = c_int
     lib.gta_profile_enable.argtypes = [c_int]
     lib.gta_profile_read.restype = c_int
@@ -272,6 +282,34 @@ def gta_spmm(plan: Plan, W, X, transposed: bool = False, Y=None):
                                    plan.n_dst, plan.n_src, heads, head_dim, code, int(bool(transposed)),
                                    _ptr(scratch), scratch.numel(), _stream()))
     return Y
+
+
+def gta_head_split(X, parts: int, S=None):
+    """X [n, H, D] -> S [parts, n, H/parts, D] (block r = heads r*H/parts .. (r+1)*H/parts)."""
+    n, heads, head_dim = X.shape
+    if S is None:
+        S = torch.empty((parts, n, max(heads // max(parts, 1), 1), head_dim), dtype=X.dtype, device=X.device)
+    _check(load_library().gta_head_split(_ptr(X), _ptr(S), n, heads, head_dim, _dtype_code(X), parts, _stream()))
+    return S
+
+
+def gta_head_merge(S, X=None):
+    """Inverse of gta_head_split: S [parts, n, H/parts, D] -> X [n, H, D]."""
+    parts, n, hp, head_dim = S.shape
+    if X is None:
+        X = torch.empty((n, hp * parts, head_dim), dtype=S.dtype, device=S.device)
+    _check(load_library().gta_head_merge(_ptr(S), _ptr(X), n, hp * parts, head_dim, _dtype_code(S), parts, _stream()))
+    return X
+
+
+def gta_agp_select(t_iter1: float, n_nodes: int, samples, max_gpus: int):
+    """samples: iterable of (strategy id, gpus, beta).  Returns (strategy, gpus, estimated t_iter)."""
+    samples = list(samples)
+    arr = (_AgpSample * max(1, len(samples)))(*[_AgpSample(int(c), int(i), float(b)) for c, i, b in samples])
+    strategy, gpus, est = c_int(), c_int(), ctypes.c_double()
+    _check(load_library().gta_agp_select(t_iter1, n_nodes, arr, len(samples), max_gpus, ctypes.byref(strategy),
+                                         ctypes.byref(gpus), ctypes.byref(est)))
+    return strategy.value, gpus.value, est.value
 
 
 def gta_profile_enable(on):

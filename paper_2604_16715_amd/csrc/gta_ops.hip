@@ -67,7 +67,7 @@ struct SddmmPass {
 template <int TEAM> struct TeamReduce {
     // combines (m, l) pairs of an online softmax over the team members that share t % H
     static __device__ __forceinline__ void softmax(float& m, float& l, int H, float* lds) {
-        for (int off = H; off < 64; off <<= 1) {
+        for (int off = H; off < (TEAM < 64 ? TEAM : 64); off <<= 1) {
             const float om = __shfl_xor(m, off), ol = __shfl_xor(l, off);
             const float mn = fmaxf(m, om);
             l = l * fast_exp2(m - mn) + ol * fast_exp2(om - mn);
@@ -90,7 +90,7 @@ template <int TEAM> struct TeamReduce {
         }
     }
     static __device__ __forceinline__ float sum(float v, int H, float* lds) {
-        for (int off = H; off < 64; off <<= 1) v += __shfl_xor(v, off);
+        for (int off = H; off < (TEAM < 64 ? TEAM : 64); off <<= 1) v += __shfl_xor(v, off);
         if (TEAM > 64) {
             const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
             __syncthreads();
@@ -245,13 +245,18 @@ extern "C" GTA_API gta_status gta_spmm(const gta_plan* plan, const int64_t* indp
 }
 
 namespace {
-template <class Launch> gta_status softmax_launches(const gta_plan* plan, const char* name, Launch launch) {
+template <class Launch> gta_status softmax_launches(const gta_plan* plan, int heads, const char* name, Launch launch) {
     const Side& sd = plan->side[0];
-    // rows above wave_max_deg: one workgroup each; the rest: one wavefront each
+    // rows above wave_max_deg: one workgroup each; short rows: 16 lanes each (when the heads fit);
+    // the rest: one wavefront each
     if (sd.n_chunked > 0) launch(std::integral_constant<int, kBlockThreads>(), (int64_t)0, sd.n_chunked, sd.n_chunked);
-    const int64_t rest = sd.n_rows - sd.n_chunked;
-    if (rest > 0)
-        launch(std::integral_constant<int, 64>(), sd.n_chunked, sd.n_rows, (rest + kWavesPerBlock - 1) / kWavesPerBlock);
+    const Split sp = make_split(plan, 0, 16);
+    const int64_t short_begin = heads <= 16 ? sp.pack_begin : sd.n_rows;
+    const int64_t mid = short_begin - sd.n_chunked, shorts = sd.n_rows - short_begin;
+    if (mid > 0)
+        launch(std::integral_constant<int, 64>(), sd.n_chunked, short_begin, (mid + kWavesPerBlock - 1) / kWavesPerBlock);
+    if (shorts > 0)
+        launch(std::integral_constant<int, 16>(), short_begin, sd.n_rows, (shorts * 16 + kBlockThreads - 1) / kBlockThreads);
     (void)name;
     GTA_HIP_TRY(hipGetLastError());
     return GTA_OK;
@@ -269,7 +274,7 @@ extern "C" GTA_API gta_status gta_edge_softmax(const gta_plan* plan, const int64
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Side& sd = plan->side[0];
     LaunchTimer t("edge_softmax", sd.n_rows, plan->nnz, st);
-    return softmax_launches(plan, "edge_softmax", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
+    return softmax_launches(plan, heads, "edge_softmax", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
         hipLaunchKernelGGL(k_edge_softmax<decltype(team)::value>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st,
                            sd.ptr, sd.bin_rows, rb, re, heads, scale * kLog2e, Z, U, lse);
     });
@@ -286,7 +291,7 @@ extern "C" GTA_API gta_status gta_edge_softmax_bwd(const gta_plan* plan, const i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Side& sd = plan->side[0];
     LaunchTimer t("edge_softmax_bwd", sd.n_rows, plan->nnz, st);
-    return softmax_launches(plan, "edge_softmax_bwd", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
+    return softmax_launches(plan, heads, "edge_softmax_bwd", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
         hipLaunchKernelGGL(k_edge_softmax_bwd<decltype(team)::value>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st,
                            sd.ptr, sd.bin_rows, rb, re, heads, scale, U, dU, dZ);
     });
