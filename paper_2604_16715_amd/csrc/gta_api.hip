@@ -65,17 +65,39 @@ gta_status make_shape(int heads, int head_dim, gta_dtype dtype, Shape* out) {
     s.head_dim = head_dim;
     s.elem_bytes = dtype == GTA_F32 ? 4 : 2;
     s.nv = 16 / s.elem_bytes;
-    const int head_bytes = head_dim * s.elem_bytes;
-    s.row_bytes = (int64_t)heads * head_bytes;
-    if (head_bytes != 32 && head_bytes != 64 && head_bytes != 128 && head_bytes != 256)
-        return fail(GTA_ERR_UNSUPPORTED, "head_dim*sizeof(element) = %d bytes; supported: 32, 64, 128, 256", head_bytes);
-    if (s.row_bytes != 128 && s.row_bytes != 256 && s.row_bytes != 512 && s.row_bytes != 1024)
-        return fail(GTA_ERR_UNSUPPORTED, "heads*head_dim*sizeof(element) = %lld bytes; supported: 128, 256, 512, 1024",
-                    (long long)s.row_bytes);
-    s.lanes_per_head = head_bytes / 16;
-    s.lanes_per_row = (int)(s.row_bytes / 16);
+    s.head_bytes = head_dim * s.elem_bytes;
+    s.row_bytes = (int64_t)heads * s.head_bytes;
+    const int hb = s.head_bytes;
+    if (hb != 16 && hb != 32 && hb != 64 && hb != 128 && hb != 256)
+        return fail(GTA_ERR_UNSUPPORTED, "head_dim*sizeof(element) = %d bytes; supported: 16, 32, 64, 128, 256", hb);
+    s.lanes_per_head = hb / 16;
+    // heads are taken slice_heads at a time: the largest power of two that divides `heads` and keeps
+    // a slice within 1024 bytes (64 lanes of 16 bytes)
+    int sh = 1;
+    while (heads % (sh * 2) == 0 && (sh * 2) * hb <= 1024) sh *= 2;
+    s.slice_heads = sh;
+    s.n_slices = heads / sh;
+    s.lanes_per_row = sh * s.lanes_per_head;
+    if (s.lanes_per_row < 4)
+        return fail(GTA_ERR_UNSUPPORTED, "heads=%d with %d-byte heads gives %d-byte slices; at least 64 bytes are needed",
+                    heads, hb, sh * hb);
     *out = s;
     return GTA_OK;
+}
+
+AttnArgs slice_args(const AttnArgs& a, int slice) {
+    AttnArgs b = a;
+    const int h0 = slice * a.shape.slice_heads;
+    const int64_t off = (int64_t)h0 * a.shape.head_bytes;
+    auto mv = [off](const void* p) { return p ? static_cast<const void*>(static_cast<const char*>(p) + off) : nullptr; };
+    auto mvw = [off](void* p) { return p ? static_cast<void*>(static_cast<char*>(p) + off) : nullptr; };
+    b.Q = mv(a.Q); b.K = mv(a.K); b.V = mv(a.V); b.out = mv(a.out); b.dO = mv(a.dO);
+    b.o_out = mvw(a.o_out); b.dQ = mvw(a.dQ); b.dK = mvw(a.dK); b.dV = mvw(a.dV);
+    if (a.lse_in) b.lse_in = a.lse_in + h0;
+    if (a.lse_out) b.lse_out = a.lse_out + h0;
+    if (a.rowstat) b.rowstat = a.rowstat + h0;
+    if (a.dS) b.dS = a.dS + h0;
+    return b;
 }
 
 Split make_split(const gta_plan* plan, int side, int lanes_per_row) {
@@ -189,7 +211,9 @@ extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* 
     a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
     a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
-    return launch_fwd(a);
+    for (int s = 0; s < sh.n_slices; ++s)
+        if ((rc = launch_fwd(slice_args(a, s))) != GTA_OK) return rc;
+    return GTA_OK;
 }
 
 extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
@@ -215,19 +239,21 @@ extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* 
     a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
     a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
-    if (scratch_bytes >= sl.total && n_dst > 0 && plan->nnz >= plan->keep_dz_min_nnz) {
-        // dZ kept per stored entry: row statistics, then dK/dV (+ dZ), then dQ as an SpMM over K
-        a.dS = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.dS);
-        if ((rc = launch_rowstat(a)) != GTA_OK) return rc;
-        if ((rc = launch_bwd_src(a)) != GTA_OK) return rc;
-        return launch_bwd_dq(a);
+    const bool keep_dz = scratch_bytes >= sl.total && n_dst > 0 && plan->nnz >= plan->keep_dz_min_nnz;
+    if (keep_dz) a.dS = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.dS);
+    for (int s = 0; s < sh.n_slices; ++s) {
+        const AttnArgs b = slice_args(a, s);
+        if (keep_dz) {
+            // dZ kept per stored entry: row statistics, then dK/dV (+ dZ), then dQ as an SpMM over K
+            if ((rc = launch_rowstat(b)) != GTA_OK) return rc;
+            if ((rc = launch_bwd_src(b)) != GTA_OK) return rc;
+            if ((rc = launch_bwd_dq(b)) != GTA_OK) return rc;
+        } else {
+            if (n_dst > 0 && (rc = launch_bwd_dst(b)) != GTA_OK) return rc;
+            if (n_src > 0 && (rc = launch_bwd_src(b)) != GTA_OK) return rc;
+        }
     }
-    if (n_dst > 0) {
-        rc = launch_bwd_dst(a);
-        if (rc != GTA_OK) return rc;
-    }
-    if (n_src > 0) rc = launch_bwd_src(a);
-    return rc;
+    return GTA_OK;
 }
 
 extern "C" GTA_API gta_status gta_profile_enable(int on) {

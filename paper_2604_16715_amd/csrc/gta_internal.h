@@ -74,11 +74,13 @@ bool split_launches();   // true while per-schedule timing (profile mode 2) is r
 
 // ---- shape handling ---------------------------------------------------------------------
 struct Shape {
-    int heads, head_dim, elem_bytes;
+    int heads, head_dim, elem_bytes;   // heads = all heads of a row (the stride of per-head arrays)
+    int head_bytes;
+    int slice_heads, n_slices;   // a row is processed in n_slices launches of slice_heads heads each
     int lanes_per_head;   // LH: 16-byte lanes covering one head
-    int lanes_per_row;    // G : 16-byte lanes covering one row
+    int lanes_per_row;    // G : 16-byte lanes covering one slice of a row (slice_heads * LH)
     int nv;               // values per lane (4 fp32, 8 bf16)
-    int64_t row_bytes;
+    int64_t row_bytes;    // all heads: the row stride
 };
 gta_status make_shape(int heads, int head_dim, gta_dtype dtype, Shape* out);
 
@@ -105,6 +107,8 @@ struct AttnArgs {
     Shape shape;
     hipStream_t stream;
 };
+
+AttnArgs slice_args(const AttnArgs& a, int slice);   // pointers moved to the slice's first head
 
 gta_status launch_fwd(const AttnArgs& a);
 gta_status launch_bwd_dst(const AttnArgs& a);

@@ -340,6 +340,10 @@ gta_status launch_pass(const char* name, const typename Pass::Params& prm, const
 // Expands to a switch over the supported (lanes per head, lanes per row) pairs.
 #define GTA_DISPATCH_GEOMETRY(LHv, Gv, CALL)                                                   \
     switch ((LHv) * 100 + (Gv)) {                                                              \
+        case 104: CALL(1, 4); break;   case 108: CALL(1, 8); break;                            \
+        case 116: CALL(1, 16); break;  case 132: CALL(1, 32); break;                           \
+        case 164: CALL(1, 64); break;  case 204: CALL(2, 4); break;                            \
+        case 404: CALL(4, 4); break;                                                           \
         case 208: CALL(2, 8); break;   case 216: CALL(2, 16); break;                           \
         case 232: CALL(2, 32); break;  case 264: CALL(2, 64); break;                           \
         case 408: CALL(4, 8); break;   case 416: CALL(4, 16); break;                           \

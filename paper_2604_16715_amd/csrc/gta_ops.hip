@@ -220,8 +220,15 @@ extern "C" GTA_API gta_status gta_sddmm(const gta_plan* plan, const int64_t* ind
     if ((rc = partial_area(plan, sh, scratch, scratch_bytes, &partial)) != GTA_OK) return rc;
     if (n_dst == 0) return GTA_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    return sh.elem_bytes == 4 ? run_sddmm<float>(plan, sh, X, Y, Z, partial, st)
-                              : run_sddmm<bf16_tag>(plan, sh, X, Y, Z, partial, st);
+    for (int s = 0; s < sh.n_slices; ++s) {
+        const int h0 = s * sh.slice_heads;
+        const char* Xs = static_cast<const char*>(X) + (int64_t)h0 * sh.head_bytes;
+        const char* Ys = static_cast<const char*>(Y) + (int64_t)h0 * sh.head_bytes;
+        rc = sh.elem_bytes == 4 ? run_sddmm<float>(plan, sh, Xs, Ys, Z + h0, partial, st)
+                                : run_sddmm<bf16_tag>(plan, sh, Xs, Ys, Z + h0, partial, st);
+        if (rc != GTA_OK) return rc;
+    }
+    return GTA_OK;
 }
 
 extern "C" GTA_API gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
@@ -240,8 +247,15 @@ extern "C" GTA_API gta_status gta_spmm(const gta_plan* plan, const int64_t* indp
     if (rows_out == 0) return GTA_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int side = transposed ? 1 : 0;
-    return sh.elem_bytes == 4 ? run_spmm<float>(plan, side, sh, W, X, Y, partial, st)
-                              : run_spmm<bf16_tag>(plan, side, sh, W, X, Y, partial, st);
+    for (int s = 0; s < sh.n_slices; ++s) {
+        const int h0 = s * sh.slice_heads;
+        const char* Xs = static_cast<const char*>(X) + (int64_t)h0 * sh.head_bytes;
+        char* Ys = static_cast<char*>(Y) + (int64_t)h0 * sh.head_bytes;
+        rc = sh.elem_bytes == 4 ? run_spmm<float>(plan, side, sh, W + h0, Xs, Ys, partial, st)
+                                : run_spmm<bf16_tag>(plan, side, sh, W + h0, Xs, Ys, partial, st);
+        if (rc != GTA_OK) return rc;
+    }
+    return GTA_OK;
 }
 
 namespace {

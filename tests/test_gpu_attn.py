@@ -56,6 +56,10 @@ def test_workloads_forced_schedules(name, shrink, kw):
     (1, 64, "f32"), (2, 64, "f32"), (8, 32, "f32"),
     (4, 16, "bf16"), (8, 16, "bf16"), (2, 32, "bf16"), (1, 64, "bf16"), (4, 128, "bf16"),
     (16, 32, "bf16"), (2, 128, "bf16"), (8, 64, "bf16"), (32, 16, "bf16"),
+    # one 16-byte lane per head, and 64-byte rows (4 lanes)
+    (8, 8, "bf16"), (16, 4, "f32"), (64, 8, "bf16"), (4, 4, "f32"), (2, 16, "bf16"), (1, 16, "f32"),
+    # rows wider than 1024 bytes and head counts that are not powers of two: several slices per row
+    (8, 64, "f32"), (16, 64, "bf16"), (3, 16, "f32"), (12, 16, "bf16"), (6, 32, "bf16"), (5, 64, "f32"),
 ])
 def test_geometries(heads, head_dim, dtype):
     indptr, indices = gen.random_csr(700, 900, 9000, seed=heads * 1000 + head_dim, allow_dup=True, sort_rows=False)
@@ -104,7 +108,8 @@ def test_unsupported_shapes_are_reported():
     import paper_2604_16715_amd as gta
     indptr, indices = gen.random_csr(16, 16, 40, seed=3)
     plan = gta.gta_plan_create(torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), 16)
-    for heads, head_dim, dt in ((3, 16, torch.float32), (4, 12, torch.float32), (64, 64, torch.bfloat16)):
+    for heads, head_dim, dt in ((4, 12, torch.float32), (2, 4, torch.bfloat16), (1, 8, torch.bfloat16),
+                                (6, 8, torch.bfloat16)):
         q = torch.zeros((16, heads, head_dim), dtype=dt, device="cuda")
         with pytest.raises(gta.GtaError) as e:
             gta.gta_attn_fwd(plan, q, q, q)

@@ -69,6 +69,8 @@ def test_operators_edge_cases():
     # unsorted rows with duplicates, empty rows, halo sources
     indptr, indices = gen.random_csr(300, 500, 4000, seed=12, allow_dup=True, sort_rows=False)
     run_ops(Problem.random(indptr, indices, 500, 2, 64, "bf16", 3), dict(wave_max_deg=16, hub_chunk=16), "ragged")
+    # sliced rows: 2048-byte rows (two slices) and 3 heads (three slices)
+    run_ops(Problem.random(indptr, indices, 500, 8, 64, "f32", 4), dict(wave_max_deg=16, hub_chunk=16), "wide rows")
     # no entries
     p = Problem.random(np.zeros(5, dtype=np.int64), np.zeros(0, dtype=np.int32), 6, 4, 16, "f32", 1)
     run_ops(p, None, "empty")
