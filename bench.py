@@ -133,6 +133,60 @@ def time_unfused(gta, torch, plan, Q, K, V, dO, w, steps, log) -> dict:
             "edge_array_bytes": 4 * E * H * 4}
 
 
+def time_layer(gta, torch, plan, w, steps, log) -> dict:
+    """One Sparse Graph Attention layer (Eq. 3-5), forward + backward: X' = X W_o + attention(X W_Q, X W_K, X W_V)."""
+    import gen
+    if w.dtype != "bf16" or w.n_src != w.n_dst:
+        return {"skipped": "the layer form needs a bf16 workload with n_src == n_dst"}
+    n, d = w.n_dst, w.heads * w.head_dim
+    dev = plan.indptr.device
+    mk = lambda shape, stream: torch.from_numpy(gen.normal(shape, "bf16", w.seed, stream).view(np.int16)).to(dev).view(torch.bfloat16)
+    X, dXout = mk((n, d), STREAM_X), mk((n, d), STREAM_DX)
+    Ws = [(mk((d, d), 10 + k).float() * (1.0 / float(np.sqrt(d)))).to(torch.bfloat16) for k in range(4)]
+
+    def step():
+        _, saved = gta.gta_sga_layer_fwd(plan, X, *Ws, w.heads)
+        gta.gta_sga_layer_bwd(plan, X, *Ws, saved, dXout, w.heads)
+
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    gta.gta_profile_enable(1)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    recs = gta.gta_profile_read(reset=True)
+    gta.gta_profile_enable(0)
+    agg: dict = {}
+    for r in recs:
+        k = agg.setdefault(r["name"], {"ms": 0.0, "calls": 0})
+        k["ms"] += r["ms"]
+        k["calls"] += 1
+    flops = 2.0 * n * d * d
+    dense_bytes = {"linear_nn": n * d * 2 * 2, "linear_nt": n * d * 2 * 2, "linear_dw": n * d * 2 * 2}
+    ops = {}
+    dense_ms = 0.0
+    for name, k in agg.items():
+        avg = k["ms"] / k["calls"]
+        entry = {"avg_ms": round(avg, 4), "calls_per_step": k["calls"] // steps}
+        if name in dense_bytes:
+            entry["tflops"] = round(flops / (avg * 1e-3) / 1e12, 1)
+            entry["gbs"] = round(dense_bytes[name] / (avg * 1e-3) / 1e9, 1)
+        if name.startswith("linear"):
+            dense_ms += k["ms"] / steps
+        ops[name] = entry
+        log(f"  layer {name:20s} {avg:9.3f} ms per call x{entry['calls_per_step']}  {entry.get('tflops', '')} TFLOP/s {entry.get('gbs', '')} GB/s")
+    return {"ms_per_step": ms, "edges_per_s": w.nnz / (ms * 1e-3), "hidden": d, "dense_ms_per_step": round(dense_ms, 3),
+            "ops": ops}
+
+
+STREAM_X, STREAM_DX = 8, 9
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -152,6 +206,9 @@ def main() -> int:
                     help="give the backward only the minimum scratch (nothing kept per stored entry)")
     ap.add_argument("--unfused", action="store_true",
                     help="also time the paper's operator-by-operator decomposition (SDDMM, softmax, SpMM ...)")
+    ap.add_argument("--layer", action="store_true",
+                    help="also time one full layer (QKV / output projections on the matrix cores + attention), "
+                         "forward and backward; bf16 workloads with n_src == n_dst only")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -266,6 +323,8 @@ def main() -> int:
     }
     if args.unfused:
         result["unfused"] = time_unfused(gta, torch, plan, Q, K, V, dO, w, args.steps, log)
+    if args.layer:
+        result["layer"] = time_layer(gta, torch, plan, w, args.steps, log)
     if not args.no_cpu_baseline:
         del Q, K, V, dO, out, dQ, dK, dV
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_edges)

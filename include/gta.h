@@ -168,6 +168,41 @@ gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* 
                     const void* X, void* Y, int64_t n_dst, int64_t n_src, int heads, int head_dim,
                     gta_dtype dtype, int transposed, void* scratch, size_t scratch_bytes, void* stream);
 
+/* ---- Dense projections of the layer on the matrix cores (Eq. 3: Q,K,V = X W_Q, X W_K, X W_V;
+ * Eq. 5: X' = X W_o + Y) and their gradients.  bfloat16 operands, fp32 accumulation; row-major,
+ * contiguous, 16-byte aligned.  d_in (the reduction length) must be a multiple of 16 and at most
+ * 512 for gta_linear, d_out a multiple of 8.
+ * gta_linear:    Y[n, d_out] = X[n, d_in] * op(W) (+ C)      C [n, d_out] may be NULL
+ *                trans_w = 0: W is [d_in, d_out] (Y = X W);   trans_w = 1: W is [d_out, d_in] (Y = X W^T,
+ *                the form of dX = dY W^T).
+ * gta_linear_dw: dW[d_in, d_out] (float) = X^T dY, X [n, d_in], dY [n, d_out]; row blocks are summed
+ *                in a fixed order (no atomics).  scratch: gta_linear_dw_scratch_bytes.             */
+gta_status gta_linear(const void* X, const void* W, const void* C, void* Y, int64_t n, int d_in, int d_out,
+                      gta_dtype dtype, int trans_w, void* stream);
+size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d_out);
+gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in, int d_out,
+                         gta_dtype dtype, void* scratch, size_t scratch_bytes, void* stream);
+
+/* ---- One Sparse Graph Attention layer (Eq. 3-5) on one GPU with n_src == n_dst == n, bfloat16:
+ *   Q,K,V = X W_Q, X W_K, X W_V;   Y = attention(Q,K,V);   X' = X W_o + Y.
+ * X, Q, K, V, Y, X' are [n, d] = [n, heads, head_dim]; weights are [d, d] (input x output).
+ * Forward writes Q, K, V, Y, lse (kept for the backward) and Xout.  Backward takes dXout and writes
+ * dX [n, d], the weight gradients dW_* (float [d, d]) and uses dQ, dK, dV [n, d] as work buffers.
+ * dX accumulates four products through bfloat16 (rounded after each).  scratch:
+ * gta_sga_layer_scratch_bytes.  Host-side sequencing of the entry points above.                  */
+size_t gta_sga_layer_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
+gta_status gta_sga_layer_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                             const void* X, const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                             void* Q, void* K, void* V, void* Y, float* lse, void* Xout, int64_t n,
+                             int heads, int head_dim, gta_dtype dtype, float scale, void* scratch,
+                             size_t scratch_bytes, void* stream);
+gta_status gta_sga_layer_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                             const void* X, const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                             const void* Q, const void* K, const void* V, const void* Y, const float* lse,
+                             const void* dXout, void* dQ, void* dK, void* dV, void* dX, float* dWq,
+                             float* dWk, float* dWv, float* dWo, int64_t n, int heads, int head_dim,
+                             gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes, void* stream);
+
 /* ---- Layout transforms of GP-A2A (Section 3.2, Algorithm 2: [(N/p),h,d'] <-> [N,(h/p),d']).
  * gta_head_split regroups X [n_rows, heads, head_dim] into `parts` contiguous blocks
  * S [parts][n_rows, heads/parts, head_dim] (block r is what GPU r receives from this GPU);

@@ -89,6 +89,18 @@ def load_library():
     for fn in (lib.gta_head_split, lib.gta_head_merge):
         fn.restype = c_int
         fn.argtypes = [vp, vp, c_int64, c_int, c_int, c_int, c_int, vp]
+    lib.gta_linear.restype = c_int
+    lib.gta_linear.argtypes = [vp, vp, vp, vp, c_int64, c_int, c_int, c_int, c_int, vp]
+    lib.gta_linear_dw_scratch_bytes.restype = c_size_t
+    lib.gta_linear_dw_scratch_bytes.argtypes = [c_int64, c_int, c_int]
+    lib.gta_linear_dw.restype = c_int
+    lib.gta_linear_dw.argtypes = [vp, vp, vp, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
+    lib.gta_sga_layer_scratch_bytes.restype = c_size_t
+    lib.gta_sga_layer_scratch_bytes.argtypes = [vp, c_int, c_int, c_int]
+    lib.gta_sga_layer_fwd.restype = c_int
+    lib.gta_sga_layer_fwd.argtypes = [vp] * 14 + [c_int64, c_int, c_int, c_int, c_float, vp, c_size_t, vp]
+    lib.gta_sga_layer_bwd.restype = c_int
+    lib.gta_sga_layer_bwd.argtypes = [vp] * 22 + [c_int64, c_int, c_int, c_int, c_float, vp, c_size_t, vp]
     lib.gta_agp_select.restype = c_int
     lib.gta_agp_select.argtypes = [ctypes.c_double, c_int64, POINTER(_AgpSample), c_int, c_int, POINTER(c_int),
                                    POINTER(c_int), POINTER(ctypes.c_double)]
@@ -282,6 +294,75 @@ def gta_spmm(plan: Plan, W, X, transposed: bool = False, Y=None):
                                    plan.n_dst, plan.n_src, heads, head_dim, code, int(bool(transposed)),
                                    _ptr(scratch), scratch.numel(), _stream()))
     return Y
+
+
+def gta_linear(X, W, C=None, trans_w: bool = False, Y=None):
+    """Y = X @ W (+ C) with W [d_in, d_out], or Y = X @ W.T (+ C) with W [d_out, d_in] when trans_w."""
+    n, d_in = X.shape
+    d_out = W.shape[0] if trans_w else W.shape[1]
+    if Y is None:
+        Y = torch.empty((n, d_out), dtype=X.dtype, device=X.device)
+    _check(load_library().gta_linear(_ptr(X), _ptr(W), _ptr(C), _ptr(Y), n, d_in, d_out, _dtype_code(X),
+                                     int(bool(trans_w)), _stream()))
+    return Y
+
+
+def gta_linear_dw(X, dY, dW=None):
+    """dW [d_in, d_out] float32 = X.T @ dY."""
+    n, d_in = X.shape
+    d_out = dY.shape[1]
+    lib = load_library()
+    if dW is None:
+        dW = torch.empty((d_in, d_out), dtype=torch.float32, device=X.device)
+    nbytes = lib.gta_linear_dw_scratch_bytes(n, d_in, d_out)
+    scratch = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)
+    _check(lib.gta_linear_dw(_ptr(X), _ptr(dY), _ptr(dW), n, d_in, d_out, _dtype_code(X), _ptr(scratch),
+                             scratch.numel(), _stream()))
+    return dW
+
+
+def _layer_scratch(plan: Plan, heads, head_dim, code):
+    key = ("layer", heads, head_dim, code)
+    if key not in plan._scratch:
+        nbytes = load_library().gta_sga_layer_scratch_bytes(plan.handle, heads, head_dim, code)
+        if nbytes == 0:
+            raise GtaError(2, "unsupported shape for the layer form")
+        plan._scratch[key] = torch.empty(nbytes, dtype=torch.uint8, device=plan.indptr.device)
+    return plan._scratch[key]
+
+
+def gta_sga_layer_fwd(plan: Plan, X, Wq, Wk, Wv, Wo, heads: int, scale: float = 0.0, saved=None):
+    """X [n, d] -> (X' [n, d], saved) with saved = dict(Q, K, V, Y, lse) for the backward."""
+    n, d = X.shape
+    head_dim = d // heads
+    code = _dtype_code(X)
+    if saved is None:
+        saved = dict(Q=torch.empty_like(X), K=torch.empty_like(X), V=torch.empty_like(X), Y=torch.empty_like(X),
+                     lse=torch.empty((n, heads), dtype=torch.float32, device=X.device))
+    Xout = torch.empty_like(X)
+    scratch = _layer_scratch(plan, heads, head_dim, code)
+    _check(load_library().gta_sga_layer_fwd(
+        plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo),
+        _ptr(saved["Q"]), _ptr(saved["K"]), _ptr(saved["V"]), _ptr(saved["Y"]), _ptr(saved["lse"]), _ptr(Xout),
+        n, heads, head_dim, code, scale, _ptr(scratch), scratch.numel(), _stream()))
+    return Xout, saved
+
+
+def gta_sga_layer_bwd(plan: Plan, X, Wq, Wk, Wv, Wo, saved, dXout, heads: int, scale: float = 0.0):
+    """Returns dX [n, d] and float32 dWq, dWk, dWv, dWo [d, d]."""
+    n, d = X.shape
+    head_dim = d // heads
+    code = _dtype_code(X)
+    work = [torch.empty_like(X) for _ in range(3)]
+    dX = torch.empty_like(X)
+    dW = [torch.empty((d, d), dtype=torch.float32, device=X.device) for _ in range(4)]
+    scratch = _layer_scratch(plan, heads, head_dim, code)
+    _check(load_library().gta_sga_layer_bwd(
+        plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo),
+        _ptr(saved["Q"]), _ptr(saved["K"]), _ptr(saved["V"]), _ptr(saved["Y"]), _ptr(saved["lse"]), _ptr(dXout),
+        _ptr(work[0]), _ptr(work[1]), _ptr(work[2]), _ptr(dX), _ptr(dW[0]), _ptr(dW[1]), _ptr(dW[2]), _ptr(dW[3]),
+        n, heads, head_dim, code, scale, _ptr(scratch), scratch.numel(), _stream()))
+    return dX, dW[0], dW[1], dW[2], dW[3]
 
 
 def gta_head_split(X, parts: int, S=None):

@@ -1,0 +1,409 @@
+// Dense projections of the layer (paper Eq. 3: Q,K,V = X W_Q, X W_K, X W_V; Eq. 5: X' = X W_o + Y)
+// and their gradients, on the matrix cores: bf16 operands, fp32 accumulation,
+// v_mfma_f32_32x32x16_bf16.  These are the only dense contractions of the layer; problem sizes
+// are n x d x d with n in the millions and d <= 512 (Section 4.1), so one operand is a tall
+// matrix streamed once from HBM and the other a small weight that lives in LDS.
+//
+// Fragment convention used throughout (lane l of a wavefront, g = l / 32):
+//   A operand: row l % 32, the 8 consecutive k values 8 g .. 8 g + 7 of the current 16-wide k step
+//   B operand: column l % 32, the same 8 k values
+//   C/D      : 16 floats; value v belongs to row 8 (v / 4) + 4 g + v % 4, column l % 32
+// A and B only have to agree with each other on which k values a lane holds.
+#include "gta_internal.h"
+
+namespace gta {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int kTile = 128;       // output tile edge of a workgroup
+constexpr int kPad = 8;          // bf16 elements of padding per LDS row (16 bytes)
+
+__device__ __forceinline__ bf16x8 as_frag(const uint4& u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ int out_row(int v, int lane) { return 8 * (v / 4) + 4 * (lane / 32) + v % 4; }
+__device__ __forceinline__ uint32_t bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_value(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// 16-bit element e (0..7) of a 16-byte unit
+__device__ __forceinline__ uint32_t half_of(const uint4& u, int e) {
+    const uint32_t wd = (e >> 1) == 0 ? u.x : (e >> 1) == 1 ? u.y : (e >> 1) == 2 ? u.z : u.w;
+    return (wd >> ((e & 1) * 16)) & 0xFFFFu;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Y[n, d_out] = X[n, d_in] * op(W) (+ C).  A workgroup owns one 64-column tile of op(W), staged in
+// LDS once ("k contiguous"); after that its four wavefronts never synchronise with each other.
+// Wavefront w walks over 32-row tiles of X (rows 32 w .. 32 w + 31 of the workgroup's 128-row
+// tiles).  X fragments come straight from global memory — a lane's 8 k values are 16 contiguous
+// bytes of its row, and the four k steps of a 128-byte line are requested together — and run one
+// full tile (at d_in = 256) ahead of the arithmetic in a register queue.  The 32 x 64 result is
+// rounded to bf16, exchanged through a per-wavefront LDS patch and written with coalesced
+// 16-byte stores; an addend C is read the same way.
+//   W_KMAJOR = true : W is stored [d_out, d_in] (Y = X W^T)   -> panel rows are copied
+//   W_KMAJOR = false: W is stored [d_in, d_out] (Y = X W)     -> panel is transposed while staged
+// Workgroups whose ids differ by 8 (same XCD) take the same row tiles for different column tiles,
+// so the rows of X they all read come out of one L2.
+constexpr int kRowsPerBlock = 128, kColsPerBlock = 64;
+constexpr int kStepsPerChunk = 8, kChunk = 16 * kStepsPerChunk, kQueue = 3;   // 3 x 8 fragments of 16 bytes in flight
+constexpr int kPatchPitch = kColsPerBlock + kPad;   // bf16 elements per row of a wavefront's 32-row LDS patch
+
+inline size_t linear_lds_bytes(int d_in) {
+    return sizeof(uint16_t) * ((size_t)kColsPerBlock * (d_in + kPad) + (size_t)kRowsPerBlock * kPatchPitch);
+}
+
+// LDS traffic between the lanes of ONE wavefront: the hardware executes a wavefront's LDS
+// instructions in order; this only stops the compiler from moving accesses across the exchange.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <bool W_KMAJOR>
+__global__ void __launch_bounds__(kThreads, 2)
+k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const uint16_t* __restrict__ C,
+         uint16_t* __restrict__ Y, int64_t n, int d_in, int d_out, int col_tiles, int64_t row_tiles,
+         int64_t groups_per_xcd) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int pitch = d_in + kPad;
+    uint16_t* panel = reinterpret_cast<uint16_t*>(lds_raw);                 // [64][d_in + kPad]
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 5, r32 = lane & 31;
+    uint16_t* patch = panel + kColsPerBlock * pitch + (32 * w) * kPatchPitch;   // this wavefront's [32][kPatchPitch]
+    const int64_t b = blockIdx.x, j = b >> 3;
+    const int xcd = (int)(b & 7);
+    const int col0 = (int)(j % col_tiles) * kColsPerBlock;
+    const int64_t group = j / col_tiles;   // 0 .. groups_per_xcd-1; row tiles (group + m * groups_per_xcd) * 8 + xcd
+
+    if (W_KMAJOR) {   // 16-byte units of the panel's rows, zero beyond d_out
+        const int units_per_k = d_in / 8;
+        for (int u = threadIdx.x; u < kColsPerBlock * units_per_k; u += kThreads) {
+            const int c = u / units_per_k, ku = u - c * units_per_k;
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (col0 + c < d_out) val = *reinterpret_cast<const uint4*>(W + (int64_t)(col0 + c) * d_in + ku * 8);
+            *reinterpret_cast<uint4*>(panel + c * pitch + ku * 8) = val;
+        }
+    } else {          // two k rows x 8 columns per step; consecutive lanes take consecutive k pairs
+        const int pairs = d_in / 2;
+        for (int u = threadIdx.x; u < pairs * (kColsPerBlock / 8); u += kThreads) {
+            const int cu = u / pairs, kp = u - cu * pairs;
+            uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+            if (col0 + cu * 8 < d_out) {
+                v0 = *reinterpret_cast<const uint4*>(W + (int64_t)(2 * kp) * d_out + col0 + cu * 8);
+                v1 = *reinterpret_cast<const uint4*>(W + (int64_t)(2 * kp + 1) * d_out + col0 + cu * 8);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<uint32_t*>(panel + (cu * 8 + e) * pitch + 2 * kp) = half_of(v0, e) | (half_of(v1, e) << 16);
+        }
+    }
+    __syncthreads();   // the only workgroup-wide synchronisation: the panel is complete
+
+    // This wavefront's work as one sequence of steps: step s = (tile m = s / chunks, chunk s % chunks).
+    const int chunks = (d_in + kChunk - 1) / kChunk;
+    const int64_t first_tile = group * 8 + xcd, tile_stride = groups_per_xcd * 8;
+    const int64_t my_tiles = first_tile < row_tiles ? (row_tiles - first_tile + tile_stride - 1) / tile_stride : 0;
+    const int64_t steps = my_tiles * chunks;
+    auto tile_row0 = [&](int64_t s) { return (first_tile + (s / chunks) * tile_stride) * kRowsPerBlock + 32 * w; };
+
+    uint4 queue[kQueue][kStepsPerChunk];   // queue[s % kQueue]: the fragments of step s
+    auto fetch = [&](uint4 (&slot)[kStepsPerChunk], int64_t s) {
+        const int64_t row = tile_row0(s) + r32;
+        const int kc = (int)(s % chunks) * kChunk;
+        const bool ok = s < steps && row < n;
+        const uint16_t* src = X + (ok ? row : 0) * d_in + kc + 8 * g;
+#pragma unroll
+        for (int i = 0; i < kStepsPerChunk; ++i) {
+            slot[i] = make_uint4(0, 0, 0, 0);
+            if (ok && kc + 16 * i < d_in) slot[i] = *reinterpret_cast<const uint4*>(src + 16 * i);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kQueue; ++i) fetch(queue[i], i);
+
+    floatx16 acc[2];
+    for (int64_t s0 = 0; s0 < steps; s0 += kQueue) {
+#pragma unroll
+        for (int qi = 0; qi < kQueue; ++qi) {
+            const int64_t s = s0 + qi;
+            if (s >= steps) break;   // uniform over the wavefront
+            const int chunk = (int)(s % chunks), kc = chunk * kChunk;
+            if (chunk == 0) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+            }
+            uint4 a[kStepsPerChunk];
+#pragma unroll
+            for (int i = 0; i < kStepsPerChunk; ++i) a[i] = queue[qi][i];
+            fetch(queue[qi], s + kQueue);
+#pragma unroll
+            for (int i = 0; i < kStepsPerChunk; ++i) {
+                const int kk = kc + 16 * i;
+                if (kk < d_in) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const uint4 bfrag = *reinterpret_cast<const uint4*>(panel + (32 * t + r32) * pitch + kk + 8 * g);
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a[i]), as_frag(bfrag), acc[t], 0, 0, 0);
+                    }
+                }
+            }
+            if (chunk != chunks - 1) continue;
+
+            // ---- 32 x 64 tile finished: (+ C), round, exchange through the patch, coalesced stores
+            const int64_t row0 = tile_row0(s);
+            if (C) {
+                wave_lds_fence();   // the patch may still be read by this wavefront's previous stores
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {   // 32 rows x 8 units of 8 columns
+                    const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+                    uint4 c = make_uint4(0, 0, 0, 0);
+                    if (row0 + r < n && col0 + cu * 8 < d_out)
+                        c = *reinterpret_cast<const uint4*>(C + (row0 + r) * d_out + col0 + cu * 8);
+                    *reinterpret_cast<uint4*>(patch + r * kPatchPitch + cu * 8) = c;
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[t][v] += bf16_value(patch[out_row(v, lane) * kPatchPitch + 32 * t + r32]);
+            }
+            wave_lds_fence();
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    patch[out_row(v, lane) * kPatchPitch + 32 * t + r32] = (uint16_t)bf16_bits(acc[t][v]);
+            wave_lds_fence();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+                if (row0 + r < n && col0 + cu * 8 < d_out)
+                    *reinterpret_cast<uint4*>(Y + (row0 + r) * d_out + col0 + cu * 8) =
+                        *reinterpret_cast<const uint4*>(patch + r * kPatchPitch + cu * 8);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dW[d_in, d_out] = X^T dY, summed over the n rows.  Workgroup: a 128 x 128 tile of dW over one
+// block of rows; wavefront (w / 2, w % 2) owns a 64 x 64 quarter.  Both operands have the
+// reduction index (the row) as their slow index, so each 32-row block is transposed into LDS:
+// a thread loads 4 consecutive rows of the same 8 columns and writes one 8-byte word per column.
+// LDS rows are 18 dwords apart and consecutive lanes write consecutive row quads, which spreads
+// both the 8-byte writes and the 8-byte fragment reads over all banks.
+// Row blocks are reduced afterwards in a fixed order (k_reduce_partials): no atomics.
+constexpr int kDwQueue = 4;
+
+__global__ void __launch_bounds__(kThreads, 2)
+k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, float* __restrict__ partial,
+            int64_t n, int d_in, int d_out, int64_t rows_per_split, int tiles_i, int tiles_o, int splits) {
+    constexpr int KB = 32, pitch = KB + 4;   // 36 bf16 = 18 dwords
+    __shared__ __align__(16) uint16_t xs[kTile * pitch], ys[kTile * pitch];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 5, r32 = lane & 31;
+    // the tiles of one row split get ids 8 apart (same XCD) so that the rows they share hit in one L2
+    const int64_t bid = blockIdx.x, jj = bid >> 3;
+    const int tiles = tiles_i * tiles_o;
+    const int tile = (int)(jj % tiles);
+    const int64_t split = (jj / tiles) * 8 + (bid & 7);
+    if (split >= splits) return;   // whole workgroup leaves together
+    const int i0 = (tile % tiles_i) * kTile, o0 = (tile / tiles_i) * kTile;
+    const int64_t rbeg = split * rows_per_split;
+    const int64_t rend = rbeg + rows_per_split < n ? rbeg + rows_per_split : n;
+    const int wi = w >> 1, wo = w & 1;
+
+    // loader role: threads 0..127 stage X, 128..255 stage dY; unit = 8 columns x 4 rows
+    const bool loads_x = threadIdx.x < 128;
+    const int lt = threadIdx.x & 127, rq = lt & 7, cu = lt >> 3;
+    const uint16_t* src = loads_x ? X : dY;
+    const int ld = loads_x ? d_in : d_out;
+    const int cbase = (loads_x ? i0 : o0) + cu * 8;
+    const bool col_ok = cbase < ld;
+    uint16_t* dst = (loads_x ? xs : ys) + (cu * 8) * pitch + rq * 4;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // register queue: the loads of row block s + kDwQueue are issued when block s is written to LDS
+    uint4 queue[kDwQueue][4];
+    auto fetch = [&](uint4 (&slot)[4], int64_t r0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t r = r0 + rq * 4 + q;
+            slot[q] = make_uint4(0, 0, 0, 0);
+            if (col_ok && r < rend) slot[q] = *reinterpret_cast<const uint4*>(src + r * ld + cbase);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kDwQueue; ++i) fetch(queue[i], rbeg + (int64_t)i * KB);
+    for (int64_t rb = rbeg; rb < rend; rb += (int64_t)kDwQueue * KB) {
+#pragma unroll
+        for (int i = 0; i < kDwQueue; ++i) {
+            const int64_t r0 = rb + (int64_t)i * KB;
+            if (r0 >= rend) break;   // uniform over the workgroup
+            __syncthreads();   // previous block's fragments have been read
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {   // column e of the unit: its four rows become one 8-byte word
+                const uint32_t lo = half_of(queue[i][0], e) | (half_of(queue[i][1], e) << 16);
+                const uint32_t hi = half_of(queue[i][2], e) | (half_of(queue[i][3], e) << 16);
+                *reinterpret_cast<uint2*>(dst + e * pitch) = make_uint2(lo, hi);
+            }
+            __syncthreads();
+            fetch(queue[i], r0 + (int64_t)kDwQueue * KB);
+#pragma unroll
+            for (int ks = 0; ks < KB; ks += 16) {
+                uint4 af[2], bf[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {   // rows are 8-byte aligned only: two 8-byte reads per fragment
+                    const uint2* pa = reinterpret_cast<const uint2*>(xs + (64 * wi + 32 * t + r32) * pitch + ks + 8 * g);
+                    const uint2* pb = reinterpret_cast<const uint2*>(ys + (64 * wo + 32 * t + r32) * pitch + ks + 8 * g);
+                    const uint2 a0 = pa[0], a1 = pa[1], b0 = pb[0], b1 = pb[1];
+                    af[t] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                    bf[t] = make_uint4(b0.x, b0.y, b1.x, b1.y);
+                }
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(af[a]), as_frag(bf[b]), acc[a][b], 0, 0, 0);
+            }
+        }
+    }
+    float* out = partial + split * d_in * d_out;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int o = o0 + 64 * wo + 32 * b + r32;
+            if (o >= d_out) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + 64 * wi + 32 * a + out_row(v, lane);
+                if (i < d_in) out[(int64_t)i * d_out + o] = acc[a][b][v];
+            }
+        }
+}
+
+__global__ void k_reduce_partials(const float* __restrict__ partial, float* __restrict__ dW, int64_t elems, int splits) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= elems) return;
+    float acc = 0.f;
+    for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * elems + i];
+    dW[i] = acc;
+}
+
+struct DwGeometry { int tiles_i, tiles_o, splits; int64_t rows_per_split; };
+
+DwGeometry dw_geometry(int64_t n, int d_in, int d_out) {
+    DwGeometry g;
+    g.tiles_i = (d_in + kTile - 1) / kTile;
+    g.tiles_o = (d_out + kTile - 1) / kTile;
+    const int64_t tiles = (int64_t)g.tiles_i * g.tiles_o;
+    int64_t splits = 512 / tiles;                       // 2 workgroups per compute unit (the register budget) in total
+    const int64_t max_splits = (n + 2047) / 2048;       // at least 2048 rows per split
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    g.rows_per_split = ((n + splits - 1) / splits + 31) / 32 * 32;
+    if (g.rows_per_split < 32) g.rows_per_split = 32;
+    g.splits = (int)((n + g.rows_per_split - 1) / g.rows_per_split);
+    if (g.splits < 1) g.splits = 1;
+    return g;
+}
+
+gta_status check_dims(int d_in, int d_out, gta_dtype dtype) {
+    if (dtype != GTA_BF16) return fail(GTA_ERR_UNSUPPORTED, "the dense projections are implemented for bfloat16 only");
+    if (d_in <= 0 || d_out <= 0 || d_in % 16 != 0 || d_out % 8 != 0)
+        return fail(GTA_ERR_UNSUPPORTED, "d_in must be a multiple of 16 and d_out a multiple of 8");
+    if (d_in > 4096 || d_out > 4096) return fail(GTA_ERR_UNSUPPORTED, "dimensions up to 4096 are supported");
+    return GTA_OK;
+}
+
+}  // namespace
+}  // namespace gta
+
+using namespace gta;
+
+extern "C" GTA_API gta_status gta_linear(const void* X, const void* W, const void* C, void* Y, int64_t n,
+                                         int d_in, int d_out, gta_dtype dtype, int trans_w, void* stream) {
+    gta_status rc = check_dims(d_in, d_out, dtype);
+    if (rc != GTA_OK) return rc;
+    if (d_in > 512) return fail(GTA_ERR_UNSUPPORTED, "d_in <= 512 is supported (the weight panel must fit in LDS)");
+    if (n < 0) return fail(GTA_ERR_INVALID_ARG, "negative size");
+    if (n == 0) return GTA_OK;
+    if (!X || !W || !Y) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (((uintptr_t)X & 15) || ((uintptr_t)W & 15)) return fail(GTA_ERR_INVALID_ARG, "X and W must be 16-byte aligned");
+    if (((uintptr_t)Y & 15) || ((uintptr_t)C & 15)) return fail(GTA_ERR_INVALID_ARG, "Y and C must be 16-byte aligned");
+    const size_t lds = linear_lds_bytes(d_in);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int col_tiles = (d_out + kColsPerBlock - 1) / kColsPerBlock;
+    const int64_t row_tiles = (n + kRowsPerBlock - 1) / kRowsPerBlock;
+    // about 512 workgroups (2 per compute unit, what the register budget allows) in total
+    int64_t groups_per_xcd = 64 / col_tiles;
+    if (groups_per_xcd < 1) groups_per_xcd = 1;
+    const int64_t max_groups = (row_tiles + 7) / 8;
+    if (groups_per_xcd > max_groups) groups_per_xcd = max_groups;
+    const int64_t blocks = groups_per_xcd * col_tiles * 8;
+    LaunchTimer t(trans_w ? "linear_nt" : "linear_nn", n, 0, st);
+    if (trans_w) {
+        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(k_linear<true>, dim3((unsigned)blocks), dim3(kThreads), lds, st, (const uint16_t*)X,
+                           (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in, d_out, col_tiles, row_tiles,
+                           groups_per_xcd);
+    } else {
+        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(k_linear<false>, dim3((unsigned)blocks), dim3(kThreads), lds, st, (const uint16_t*)X,
+                           (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in, d_out, col_tiles, row_tiles,
+                           groups_per_xcd);
+    }
+    GTA_HIP_TRY(hipGetLastError());
+    return GTA_OK;
+}
+
+extern "C" GTA_API size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d_out) {
+    if (n < 0 || d_in <= 0 || d_out <= 0) return 0;
+    const DwGeometry g = dw_geometry(n, d_in, d_out);
+    return sizeof(float) * (size_t)g.splits * (size_t)d_in * (size_t)d_out + 256;
+}
+
+extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in,
+                                            int d_out, gta_dtype dtype, void* scratch, size_t scratch_bytes,
+                                            void* stream) {
+    gta_status rc = check_dims(d_in, d_out, dtype);
+    if (rc != GTA_OK) return rc;
+    if (n < 0) return fail(GTA_ERR_INVALID_ARG, "negative size");
+    if (!dW) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (n > 0 && (!X || !dY)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (((uintptr_t)X & 15) || ((uintptr_t)dY & 15)) return fail(GTA_ERR_INVALID_ARG, "X and dY must be 16-byte aligned");
+    const size_t need = gta_linear_dw_scratch_bytes(n, d_in, d_out);
+    if (!scratch || scratch_bytes < need) return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const DwGeometry g = dw_geometry(n, d_in, d_out);
+    const int64_t elems = (int64_t)d_in * d_out;
+    float* partial = static_cast<float*>(scratch);
+    {
+        LaunchTimer t("linear_dw", n, 0, st);
+        const int64_t blocks = (int64_t)(g.splits + 7) / 8 * 8 * g.tiles_i * g.tiles_o;
+        hipLaunchKernelGGL(k_linear_dw, dim3((unsigned)blocks), dim3(kThreads), 0, st, (const uint16_t*)X,
+                           (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split, g.tiles_i, g.tiles_o, g.splits);
+    }
+    {
+        LaunchTimer t("linear_dw.reduce", 0, 0, st);
+        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, partial, dW,
+                           elems, g.splits);
+    }
+    GTA_HIP_TRY(hipGetLastError());
+    return GTA_OK;
+}

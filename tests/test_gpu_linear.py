@@ -1,0 +1,62 @@
+"""MFMA projections (X W, X W^T, X^T dY) against the float64 reference."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+from helpers import assert_close, to_f64, to_torch
+from oracle import dense_ref
+
+pytestmark = pytest.mark.gpu
+
+
+def bf16_matrix(rows, cols, seed, stream, scale=1.0):
+    x = gen.normal((rows, cols), "bf16", seed, stream)
+    if scale != 1.0:
+        f = (gen.bf16_bits_to_f32(x) * scale).astype(np.float32)
+        x = (f.view(np.uint32) >> 16).astype(np.uint16)   # truncation keeps the values exactly representable
+    return x
+
+
+@pytest.mark.parametrize("n,d_in,d_out", [
+    (1000, 128, 128), (4097, 256, 256), (333, 64, 64), (2048, 256, 768), (513, 128, 384), (129, 512, 512),
+    (64, 16, 8), (1, 32, 40), (5000, 48, 200),
+])
+def test_linear_forward_forms(n, d_in, d_out):
+    import paper_2604_16715_amd as gta
+    print(f"linear case n={n} d_in={d_in} d_out={d_out}", flush=True)
+    X, W, C = bf16_matrix(n, d_in, 1, 2), bf16_matrix(d_in, d_out, 1, 3, 0.125), bf16_matrix(n, d_out, 1, 4)
+    Xf, Wf, Cf = (gen.bf16_bits_to_f32(a).astype(np.float64) for a in (X, W, C))
+    Xd, Wd, Cd = to_torch(X), to_torch(W), to_torch(C)
+    assert_close("X W", to_f64(gta.gta_linear(Xd, Wd)), dense_ref.linear(Xf, Wf), 2e-2)
+    assert_close("X W + C", to_f64(gta.gta_linear(Xd, Wd, Cd)), dense_ref.linear(Xf, Wf, Cf), 2e-2)
+    Wt = to_torch(np.ascontiguousarray(W.T))
+    assert_close("X W^T form", to_f64(gta.gta_linear(Xd, Wt, Cd, trans_w=True)), dense_ref.linear(Xf, Wf, Cf), 2e-2)
+    # results of the two storage forms of W are the same bits: same products, same order
+    assert torch.equal(gta.gta_linear(Xd, Wd, Cd).view(torch.int16), gta.gta_linear(Xd, Wt, Cd, trans_w=True).view(torch.int16))
+
+
+@pytest.mark.parametrize("n,d_in,d_out", [
+    (1000, 128, 128), (70000, 256, 256), (333, 64, 192), (31, 16, 8), (4096, 512, 128), (5000, 48, 200),
+])
+def test_linear_weight_gradient(n, d_in, d_out):
+    import paper_2604_16715_amd as gta
+    print(f"linear_dw case n={n} d_in={d_in} d_out={d_out}", flush=True)
+    X, dY = bf16_matrix(n, d_in, 2, 2), bf16_matrix(n, d_out, 2, 5)
+    Xf, dYf = (gen.bf16_bits_to_f32(a).astype(np.float64) for a in (X, dY))
+    got = gta.gta_linear_dw(to_torch(X), to_torch(dY))
+    assert_close("X^T dY", to_f64(got), dense_ref.linear_dw(Xf, dYf), 1e-4)
+    again = gta.gta_linear_dw(to_torch(X), to_torch(dY))
+    assert torch.equal(got, again), "weight gradient is not bitwise reproducible"
+
+
+def test_linear_rejects_unsupported():
+    import paper_2604_16715_amd as gta
+    X = torch.zeros((8, 24), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((24, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear(X, W)                     # d_in not a multiple of 16
+    X = torch.zeros((8, 32), dtype=torch.float32, device="cuda")
+    W = torch.zeros((32, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear(X, W)                     # fp32 not implemented for the projections
