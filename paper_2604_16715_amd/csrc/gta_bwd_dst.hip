@@ -31,26 +31,25 @@ struct BwdDstPass {
         float qscale, scale;
         int heads;
     };
-    float q[NV], go[NV];
+    uint4 qraw, graw;   // this lane's 16 bytes of the row's query and output-gradient, as stored
+    float qscale;
     float lse2, delta;
     float f[N];
     uint4 kr[U], vr[U];
 
     __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool primary) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) { q[i] = 0.f; go[i] = 0.f; f[i] = 0.f; }
+        for (int i = 0; i < NV; ++i) f[i] = 0.f;
         lse2 = 0.f;
         delta = 0.f;
+        qscale = p.qscale;
+        qraw = make_uint4(0, 0, 0, 0);
+        graw = make_uint4(0, 0, 0, 0);
         if (active) {
-            float o[NV];
-            Elt<T>::unpack(load16(p.Q, row, p.stride, lig), q);
-            Elt<T>::unpack(load16(p.dO, row, p.stride, lig), go);
-            Elt<T>::unpack(load16(p.out, row, p.stride, lig), o);
-            float d = 0.f;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) { d = fmaf(go[i], o[i], d); q[i] *= p.qscale; }
+            qraw = load16(p.Q, row, p.stride, lig);
+            graw = load16(p.dO, row, p.stride, lig);
+            delta = Elt<T>::dot(graw, load16(p.out, row, p.stride, lig));
             lse2 = p.lse[(int64_t)row * p.heads + lig / LH] * kLog2e;
-            delta = d;
         }
         delta = head_allreduce<LH>(delta);
         if (active && primary && lig % LH == 0)
@@ -67,14 +66,10 @@ struct BwdDstPass {
     __device__ __forceinline__ void compute(const bool (&ok)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float k[NV], v[NV];
+            float k[NV];
             Elt<T>::unpack(kr[u], k);
-            Elt<T>::unpack(vr[u], v);
-            float s = 0.f, da = 0.f;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) { s = fmaf(q[i], k[i], s); da = fmaf(go[i], v[i], da); }
-            s = head_allreduce<LH>(s);
-            da = head_allreduce<LH>(da);
+            const float s = head_allreduce<LH>(Elt<T>::dot(qraw, kr[u])) * qscale;
+            const float da = head_allreduce<LH>(Elt<T>::dot(graw, vr[u]));
             const float a = ok[u] ? fast_exp2(s - lse2) : 0.f;
             const float dz = a * (da - delta);
 #pragma unroll
@@ -98,16 +93,11 @@ template <class T, int LH, int G>
 __global__ void __launch_bounds__(kBlockThreads)
 k_rowstat(const char* out, const char* dO, const float* lse, float2* rowstat, int64_t n_rows, int64_t stride,
           int heads) {
-    constexpr int NV = Elt<T>::NV;
     const int64_t row = ((int64_t)blockIdx.x * kBlockThreads + threadIdx.x) / G;
     const int lig = threadIdx.x % G;
     float d = 0.f;
     if (row < n_rows) {
-        float o[NV], go[NV];
-        Elt<T>::unpack(load16(out, row, stride, lig), o);
-        Elt<T>::unpack(load16(dO, row, stride, lig), go);
-#pragma unroll
-        for (int i = 0; i < NV; ++i) d = fmaf(go[i], o[i], d);
+        d = Elt<T>::dot(load16(dO, row, stride, lig), load16(out, row, stride, lig));
     }
     d = head_allreduce<LH>(d);
     if (row < n_rows && lig % LH == 0)

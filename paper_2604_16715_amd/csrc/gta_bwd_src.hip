@@ -28,7 +28,8 @@ struct BwdSrcPass {
         float qscale, scale;
         int heads;
     };
-    float k2[NV], v[NV];
+    uint4 kraw, vraw;   // this lane's 16 bytes of the source's key and value rows, as stored
+    float qscale;
     float f[N];
     uint4 qr[U], gr[U];
     float2 st[U];
@@ -38,15 +39,16 @@ struct BwdSrcPass {
 
     __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) { k2[i] = 0.f; v[i] = 0.f; f[i] = 0.f; f[NV + i] = 0.f; }
+        for (int i = 0; i < NV; ++i) { f[i] = 0.f; f[NV + i] = 0.f; }
+        kraw = make_uint4(0, 0, 0, 0);
+        vraw = make_uint4(0, 0, 0, 0);
+        qscale = p.qscale;
         ds_out = p.dS;
         n_heads = p.heads;
         my_lig = lig;
         if (active) {
-            Elt<T>::unpack(load16(p.K, row, p.stride, lig), k2);
-            Elt<T>::unpack(load16(p.V, row, p.stride, lig), v);
-#pragma unroll
-            for (int i = 0; i < NV; ++i) k2[i] *= p.qscale;
+            kraw = load16(p.K, row, p.stride, lig);
+            vraw = load16(p.V, row, p.stride, lig);
         }
     }
     __device__ __forceinline__ void load(const Params& p, int u, int i, int e, bool ok, int lig) {
@@ -66,11 +68,8 @@ struct BwdSrcPass {
             float q[NV], go[NV];
             Elt<T>::unpack(qr[u], q);
             Elt<T>::unpack(gr[u], go);
-            float s = 0.f, da = 0.f;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) { s = fmaf(q[i], k2[i], s); da = fmaf(go[i], v[i], da); }
-            s = head_allreduce<LH>(s);
-            da = head_allreduce<LH>(da);
+            const float s = head_allreduce<LH>(Elt<T>::dot(qr[u], kraw)) * qscale;
+            const float da = head_allreduce<LH>(Elt<T>::dot(gr[u], vraw));
             const float a = ok[u] ? fast_exp2(s - st[u].x) : 0.f;
             const float dz = a * (da - st[u].y);
             if (STORE && ok[u] && my_lig % LH == 0) ds_out[(int64_t)eids[u] * n_heads + my_lig / LH] = dz;

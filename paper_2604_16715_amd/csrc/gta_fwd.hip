@@ -22,20 +22,19 @@ struct FwdPass {
         float qscale;   // scale * log2(e)
         int heads;
     };
-    float q[NV];
+    uint4 q;         // this lane's 16 bytes of the query row, as stored
+    float qscale;
     float f[N];
     uint4 kr[U], vr[U];
 
     __device__ __forceinline__ void init(const Params& p, int row, int lig, bool active, bool) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) { q[i] = 0.f; f[i] = 0.f; }
+        for (int i = 0; i < NV; ++i) f[i] = 0.f;
         f[NV] = kNegBig;
         f[NV + 1] = 0.f;
-        if (active) {
-            Elt<T>::unpack(load16(p.Q, row, p.stride, lig), q);
-#pragma unroll
-            for (int i = 0; i < NV; ++i) q[i] *= p.qscale;
-        }
+        qscale = p.qscale;
+        q = make_uint4(0, 0, 0, 0);
+        if (active) q = load16(p.Q, row, p.stride, lig);
     }
     __device__ __forceinline__ void load(const Params& p, int u, int j, int, bool ok, int lig) {
         kr[u] = make_uint4(0, 0, 0, 0);
@@ -50,12 +49,7 @@ struct FwdPass {
         float mn = f[NV];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float k[NV];
-            Elt<T>::unpack(kr[u], k);
-            float d = 0.f;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) d = fmaf(q[i], k[i], d);
-            d = head_allreduce<LH>(d);
+            const float d = head_allreduce<LH>(Elt<T>::dot(q, kr[u])) * qscale;
             s[u] = ok[u] ? d : -INFINITY;
             mn = fmaxf(mn, s[u]);
         }

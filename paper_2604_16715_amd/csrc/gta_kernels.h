@@ -40,6 +40,13 @@ template <> struct Elt<float> {
     static __device__ __forceinline__ uint4 pack(const float (&x)[4]) {
         return make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3]));
     }
+    // sum of the 4 products of two 16-byte units
+    static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
+        float d = __uint_as_float(a.x) * __uint_as_float(b.x);
+        d = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), d);
+        d = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), d);
+        return fmaf(__uint_as_float(a.w), __uint_as_float(b.w), d);
+    }
 };
 __device__ __forceinline__ uint32_t bf16_round(float x) {   // round to nearest even, upper 16 bits
     uint32_t u = __float_as_uint(x);
@@ -62,6 +69,16 @@ template <> struct Elt<bf16_tag> {
 #pragma unroll
         for (int k = 0; k < 4; ++k) w[k] = bf16_round(x[2 * k]) | (bf16_round(x[2 * k + 1]) << 16);
         return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    // sum of the 8 products of two 16-byte units, on the packed pairs (v_dot2c_f32_bf16: each
+    // product is exact in fp32, accumulation is fp32)
+    static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        float d = 0.f;
+        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), d, false);
+        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), d, false);
+        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), d, false);
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), d, false);
     }
 };
 
@@ -109,8 +126,8 @@ struct ChunkSet {
 // position of entry `pos` in the caller's per-entry arrays, for passes that read or write them
 template <class Pass>
 __device__ __forceinline__ int entry_id(const int32_t* eid, int pos, bool valid) {
-    if (!Pass::kUsesEntryId || !valid) return 0;
-    return eid ? eid[pos] : pos;
+    if (!Pass::kUsesEntryId || !valid || !eid) return 0;
+    return eid[pos];
 }
 
 // One batch of up to 64 consecutive entries held one per lane (slot t lives in lane lane_base+t).
@@ -119,7 +136,8 @@ __device__ __forceinline__ int entry_id(const int32_t* eid, int pos, bool valid)
 // name a lane that has already left it.
 template <class Pass>
 __device__ __forceinline__ void run_batch(Pass& ps, const typename Pass::Params& prm, int my_idx, int my_eid,
-                                          int nb, int lane_base, int first, int stride, int lig) {
+                                          bool mapped, int base, int nb, int lane_base, int first, int stride,
+                                          int lig) {
     constexpr int U = Pass::U;
     for (int t0 = 0; t0 < nb; t0 += U * stride) {
         bool ok[U];
@@ -128,7 +146,8 @@ __device__ __forceinline__ void run_batch(Pass& ps, const typename Pass::Params&
             const int t = t0 + u * stride + first;
             ok[u] = t < nb;
             const int j = __shfl(my_idx, (lane_base + t) & 63);
-            const int e = Pass::kUsesEntryId ? __shfl(my_eid, (lane_base + t) & 63) : 0;
+            // entry id of slot t: through the map if there is one, else its position base + t
+            const int e = !Pass::kUsesEntryId ? 0 : mapped ? __shfl(my_eid, (lane_base + t) & 63) : base + t;
             ps.load(prm, u, j, e, ok[u], lig);
         }
         ps.compute(ok);
@@ -168,7 +187,7 @@ __device__ __forceinline__ void body_packed(const typename Pass::Params& prm, co
         const int nb = min(G, e - bb);
         const int my = lig < nb ? rs.idx[bb + lig] : 0;
         const int my_e = entry_id<Pass>(rs.eid, bb + lig, lig < nb);
-        run_batch(ps, prm, my, my_e, nb, g * G, 0, 1, lig);
+        run_batch(ps, prm, my, my_e, rs.eid != nullptr, bb, nb, g * G, 0, 1, lig);
     }
     if (active) Pass::finish(prm, row, lig, ps.f);
 }
@@ -187,7 +206,7 @@ __device__ __forceinline__ void body_wave(const typename Pass::Params& prm, cons
         const int nb = min(64, e - bb);
         const int my = lane < nb ? rs.idx[bb + lane] : 0;
         const int my_e = entry_id<Pass>(rs.eid, bb + lane, lane < nb);
-        run_batch(ps, prm, my, my_e, nb, 0, g, W, lig);
+        run_batch(ps, prm, my, my_e, rs.eid != nullptr, bb, nb, 0, g, W, lig);
     }
     wave_merge<Pass>(ps.f);
     if (g == 0) Pass::finish(prm, row, lig, ps.f);
@@ -207,7 +226,7 @@ __device__ __forceinline__ void body_chunk(const typename Pass::Params& prm, con
         const int nb = min(64, ce - bb);
         const int my = lane < nb ? cs.idx[bb + lane] : 0;
         const int my_e = entry_id<Pass>(cs.eid, bb + lane, lane < nb);
-        run_batch(ps, prm, my, my_e, nb, 0, g, W, lig);
+        run_batch(ps, prm, my, my_e, cs.eid != nullptr, bb, nb, 0, g, W, lig);
     }
     wave_merge<Pass>(ps.f);
     if (w > 0 && g == 0) {
