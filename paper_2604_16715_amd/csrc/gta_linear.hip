@@ -41,8 +41,7 @@ __device__ __forceinline__ uint32_t half_of(const uint4& u, int e) {
 // LDS once ("k contiguous"); after that its four wavefronts never synchronise with each other.
 // Wavefront w walks over 32-row tiles of X (rows 32 w .. 32 w + 31 of the workgroup's 128-row
 // tiles).  X fragments come straight from global memory — a lane's 8 k values are 16 contiguous
-// bytes of its row, and the four k steps of a 128-byte line are requested together — and run one
-// full tile (at d_in = 256) ahead of the arithmetic in a register queue.  The 32 x 64 result is
+// bytes of its row — and run one full tile ahead of the arithmetic in registers.  The 32 x 64 result is
 // rounded to bf16, exchanged through a per-wavefront LDS patch and written with coalesced
 // 16-byte stores; an addend C is read the same way.
 //   W_KMAJOR = true : W is stored [d_out, d_in] (Y = X W^T)   -> panel rows are copied
@@ -50,11 +49,12 @@ __device__ __forceinline__ uint32_t half_of(const uint4& u, int e) {
 // Workgroups whose ids differ by 8 (same XCD) take the same row tiles for different column tiles,
 // so the rows of X they all read come out of one L2.
 constexpr int kRowsPerBlock = 128, kColsPerBlock = 64;
-constexpr int kStepsPerChunk = 8, kChunk = 16 * kStepsPerChunk, kQueue = 3;   // 3 x 8 fragments of 16 bytes in flight
-constexpr int kPatchPitch = kColsPerBlock + kPad;   // bf16 elements per row of a wavefront's 32-row LDS patch
+constexpr int kStepsPerChunk = 8;                   // k steps (of 16) staged per chunk
+constexpr int kPatchPitch = kColsPerBlock + kPad;   // bf16 elements per row of a wavefront's 32-row result patch
+constexpr int kStagePitch = 16 * kStepsPerChunk + kPad;   // ... and of its X stage (which the patch reuses)
 
 inline size_t linear_lds_bytes(int d_in) {
-    return sizeof(uint16_t) * ((size_t)kColsPerBlock * (d_in + kPad) + (size_t)kRowsPerBlock * kPatchPitch);
+    return sizeof(uint16_t) * ((size_t)kColsPerBlock * (d_in + kPad) + (size_t)kRowsPerBlock * kStagePitch);
 }
 
 // LDS traffic between the lanes of ONE wavefront: the hardware executes a wavefront's LDS
@@ -65,16 +65,23 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool W_KMAJOR>
-__global__ void __launch_bounds__(kThreads, 2)
+// KSTEPS = d_in / 16 at compile time for d_in = 64, 128, 256 (0: any d_in, read from the argument,
+// without run-ahead).  With a compile-time reduction length every load of the main loop is
+// unconditional and branch-free, which is what lets the compiler count outstanding loads exactly
+// instead of waiting for all of them before each MFMA (rows past the end are clamped to the last
+// row; their results are never stored).
+template <bool W_KMAJOR, int KSTEPS>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const uint16_t* __restrict__ C,
-         uint16_t* __restrict__ Y, int64_t n, int d_in, int d_out, int col_tiles, int64_t row_tiles,
+         uint16_t* __restrict__ Y, int64_t n, int d_in_arg, int d_out, int col_tiles, int64_t row_tiles,
          int64_t groups_per_xcd) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int d_in = KSTEPS > 0 ? KSTEPS * 16 : d_in_arg;
     const int pitch = d_in + kPad;
     uint16_t* panel = reinterpret_cast<uint16_t*>(lds_raw);                 // [64][d_in + kPad]
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 5, r32 = lane & 31;
-    uint16_t* patch = panel + kColsPerBlock * pitch + (32 * w) * kPatchPitch;   // this wavefront's [32][kPatchPitch]
+    uint16_t* stage = panel + kColsPerBlock * pitch + (32 * w) * kStagePitch;   // this wavefront's [32][kStagePitch]
+    uint16_t* patch = stage;                                                    // the result patch reuses it
     const int64_t b = blockIdx.x, j = b >> 3;
     const int xcd = (int)(b & 7);
     const int col0 = (int)(j % col_tiles) * kColsPerBlock;
@@ -104,91 +111,131 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
     }
     __syncthreads();   // the only workgroup-wide synchronisation: the panel is complete
 
-    // This wavefront's work as one sequence of steps: step s = (tile m = s / chunks, chunk s % chunks).
-    const int chunks = (d_in + kChunk - 1) / kChunk;
+    // 32-row tiles of this wavefront: rows 32 w .. of the 128-row tiles (group + m * groups_per_xcd) * 8 + xcd
     const int64_t first_tile = group * 8 + xcd, tile_stride = groups_per_xcd * 8;
     const int64_t my_tiles = first_tile < row_tiles ? (row_tiles - first_tile + tile_stride - 1) / tile_stride : 0;
-    const int64_t steps = my_tiles * chunks;
-    auto tile_row0 = [&](int64_t s) { return (first_tile + (s / chunks) * tile_stride) * kRowsPerBlock + 32 * w; };
-
-    uint4 queue[kQueue][kStepsPerChunk];   // queue[s % kQueue]: the fragments of step s
-    auto fetch = [&](uint4 (&slot)[kStepsPerChunk], int64_t s) {
-        const int64_t row = tile_row0(s) + r32;
-        const int kc = (int)(s % chunks) * kChunk;
-        const bool ok = s < steps && row < n;
-        const uint16_t* src = X + (ok ? row : 0) * d_in + kc + 8 * g;
-#pragma unroll
-        for (int i = 0; i < kStepsPerChunk; ++i) {
-            slot[i] = make_uint4(0, 0, 0, 0);
-            if (ok && kc + 16 * i < d_in) slot[i] = *reinterpret_cast<const uint4*>(src + 16 * i);
-        }
+    if (my_tiles == 0) return;
+    auto tile_row0 = [&](int64_t m) { return (first_tile + m * tile_stride) * kRowsPerBlock + 32 * w; };
+    auto lane_src = [&](int64_t m) {   // this lane's row of tile m (clamped: such rows are computed, never stored)
+        int64_t row = tile_row0(m < my_tiles ? m : my_tiles - 1) + r32;
+        if (row >= n) row = n - 1;
+        return X + row * d_in + 8 * g;
     };
-#pragma unroll
-    for (int i = 0; i < kQueue; ++i) fetch(queue[i], i);
-
     floatx16 acc[2];
-    for (int64_t s0 = 0; s0 < steps; s0 += kQueue) {
-#pragma unroll
-        for (int qi = 0; qi < kQueue; ++qi) {
-            const int64_t s = s0 + qi;
-            if (s >= steps) break;   // uniform over the wavefront
-            const int chunk = (int)(s % chunks), kc = chunk * kChunk;
-            if (chunk == 0) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-            }
-            uint4 a[kStepsPerChunk];
-#pragma unroll
-            for (int i = 0; i < kStepsPerChunk; ++i) a[i] = queue[qi][i];
-            fetch(queue[qi], s + kQueue);
-#pragma unroll
-            for (int i = 0; i < kStepsPerChunk; ++i) {
-                const int kk = kc + 16 * i;
-                if (kk < d_in) {
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const uint4 bfrag = *reinterpret_cast<const uint4*>(panel + (32 * t + r32) * pitch + kk + 8 * g);
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a[i]), as_frag(bfrag), acc[t], 0, 0, 0);
-                    }
-                }
-            }
-            if (chunk != chunks - 1) continue;
 
-            // ---- 32 x 64 tile finished: (+ C), round, exchange through the patch, coalesced stores
-            const int64_t row0 = tile_row0(s);
-            if (C) {
-                wave_lds_fence();   // the patch may still be read by this wavefront's previous stores
+    auto finish_tile = [&](int64_t m) {   // (+ C), round, exchange through the patch, coalesced stores
+        const int64_t row0 = tile_row0(m);
+        if (C) {
+            wave_lds_fence();   // the patch may still be read by this wavefront's previous stores
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {   // 32 rows x 8 units of 8 columns
-                    const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
-                    uint4 c = make_uint4(0, 0, 0, 0);
-                    if (row0 + r < n && col0 + cu * 8 < d_out)
-                        c = *reinterpret_cast<const uint4*>(C + (row0 + r) * d_out + col0 + cu * 8);
-                    *reinterpret_cast<uint4*>(patch + r * kPatchPitch + cu * 8) = c;
-                }
-                wave_lds_fence();
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        acc[t][v] += bf16_value(patch[out_row(v, lane) * kPatchPitch + 32 * t + r32]);
+            for (int q = 0; q < 4; ++q) {   // 32 rows x 8 units of 8 columns
+                const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+                uint4 c = make_uint4(0, 0, 0, 0);
+                if (row0 + r < n && col0 + cu * 8 < d_out)
+                    c = *reinterpret_cast<const uint4*>(C + (row0 + r) * d_out + col0 + cu * 8);
+                *reinterpret_cast<uint4*>(patch + r * kPatchPitch + cu * 8) = c;
             }
             wave_lds_fence();
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    patch[out_row(v, lane) * kPatchPitch + 32 * t + r32] = (uint16_t)bf16_bits(acc[t][v]);
-            wave_lds_fence();
+                    acc[t][v] += bf16_value(patch[out_row(v, lane) * kPatchPitch + 32 * t + r32]);
+        }
+        wave_lds_fence();
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
-                if (row0 + r < n && col0 + cu * 8 < d_out)
-                    *reinterpret_cast<uint4*>(Y + (row0 + r) * d_out + col0 + cu * 8) =
-                        *reinterpret_cast<const uint4*>(patch + r * kPatchPitch + cu * 8);
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                patch[out_row(v, lane) * kPatchPitch + 32 * t + r32] = (uint16_t)bf16_bits(acc[t][v]);
+        wave_lds_fence();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+            if (row0 + r < n && col0 + cu * 8 < d_out)
+                *reinterpret_cast<uint4*>(Y + (row0 + r) * d_out + col0 + cu * 8) =
+                    *reinterpret_cast<const uint4*>(patch + r * kPatchPitch + cu * 8);
+        }
+    };
+
+    if constexpr (KSTEPS > 0) {
+        // X goes global -> registers -> this wavefront's LDS stage -> MFMA fragments, in chunks of
+        // up to 8 k steps (256 bytes per row).  The global loads are fully coalesced (a load
+        // instruction covers 4 rows x 256 contiguous bytes = 8 whole cache lines; reading the
+        // fragments directly would touch 32 lines per instruction and is bound by the L1's line
+        // rate) and run two chunks — one tile at d_in = 256 — ahead in two register sets.
+        constexpr int CS = KSTEPS < kStepsPerChunk ? KSTEPS : kStepsPerChunk;   // k steps per chunk
+        constexpr int CHUNKS = KSTEPS / CS;
+        constexpr int UNITS = CS * 2;                    // 16-byte units per row of a chunk
+        constexpr int ROWS_PER_LOAD = 64 / UNITS;        // rows one load instruction covers
+        constexpr int LOADS = 32 / ROWS_PER_LOAD;        // load instructions per chunk
+        const int64_t steps = my_tiles * CHUNKS;         // step s = (tile s / CHUNKS, chunk s % CHUNKS)
+        const int urow = lane / UNITS, ucol = lane % UNITS;
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 set0[LOADS], set1[LOADS];   // the units of the even / odd steps (then of the step two later)
+#define GTA_FETCH(SET, STEP)                                                                   \
+        {                                                                                          \
+            int64_t fs = (STEP);                                                                   \
+            if (fs >= steps) fs = steps - 1; /* past the end: re-read the last chunk (unused) */  \
+            const int64_t frow0 = tile_row0(fs / CHUNKS);                                          \
+            const int fkc = (int)(fs % CHUNKS) * (16 * CS);                                        \
+            _Pragma("unroll") for (int q = 0; q < LOADS; ++q) {                                    \
+                int64_t row = frow0 + q * ROWS_PER_LOAD + urow;                                    \
+                if (row >= n) row = n - 1; /* clamped rows are computed but never stored */       \
+                SET[q] = *reinterpret_cast<const u32x4*>(X + row * d_in + fkc + 8 * ucol);         \
+            }                                                                                      \
+        }
+#define GTA_STEP(SET, STEP)                                                                        \
+        {                                                                                          \
+            const int64_t s = (STEP);                                                              \
+            const int chunk = (int)(s % CHUNKS);                                                   \
+            wave_lds_fence(); /* earlier fragment / patch reads of this wavefront are issued */    \
+            _Pragma("unroll") for (int q = 0; q < LOADS; ++q)                                      \
+                *reinterpret_cast<u32x4*>(stage + (q * ROWS_PER_LOAD + urow) * kStagePitch + 8 * ucol) = SET[q]; \
+            GTA_FETCH(SET, s + 2)                                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                     \
+            wave_lds_fence();                                                                      \
+            if (chunk == 0) {                                                                      \
+                _Pragma("unroll") for (int t = 0; t < 2; ++t)                                      \
+                    _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;                \
+            }                                                                                      \
+            const uint16_t* wrow = panel + r32 * pitch + chunk * (16 * CS) + 8 * g;                \
+            const uint16_t* arow = stage + r32 * kStagePitch + 8 * g;                              \
+            _Pragma("unroll") for (int i = 0; i < CS; ++i) {                                       \
+                const uint4 a = *reinterpret_cast<const uint4*>(arow + 16 * i);                    \
+                const uint4 b0 = *reinterpret_cast<const uint4*>(wrow + 16 * i);                   \
+                const uint4 b1 = *reinterpret_cast<const uint4*>(wrow + 32 * pitch + 16 * i);      \
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(b0), acc[0], 0, 0, 0); \
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(b1), acc[1], 0, 0, 0); \
+            }                                                                                      \
+            if (chunk == CHUNKS - 1) finish_tile(s / CHUNKS);                                      \
+        }
+        GTA_FETCH(set0, 0)
+        GTA_FETCH(set1, 1)
+        for (int64_t s0 = 0; s0 < steps; s0 += 2) {
+            GTA_STEP(set0, s0)
+            if (s0 + 1 < steps) GTA_STEP(set1, s0 + 1)
+        }
+#undef GTA_STEP
+#undef GTA_FETCH
+    } else {
+        // any reduction length: fragments are fetched when needed (no run-ahead)
+        const int ksteps = d_in / 16;
+        for (int64_t m = 0; m < my_tiles; ++m) {
+            const uint16_t* src = lane_src(m);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+            for (int i = 0; i < ksteps; ++i) {
+                const uint4 a = *reinterpret_cast<const uint4*>(src + 16 * i);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const uint4 bfrag = *reinterpret_cast<const uint4*>(panel + (32 * t + r32) * pitch + 16 * i + 8 * g);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(bfrag), acc[t], 0, 0, 0);
+                }
             }
+            finish_tile(m);
         }
     }
 }
@@ -357,17 +404,24 @@ extern "C" GTA_API gta_status gta_linear(const void* X, const void* W, const voi
     if (groups_per_xcd > max_groups) groups_per_xcd = max_groups;
     const int64_t blocks = groups_per_xcd * col_tiles * 8;
     LaunchTimer t(trans_w ? "linear_nt" : "linear_nn", n, 0, st);
-    if (trans_w) {
-        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(k_linear<true>, dim3((unsigned)blocks), dim3(kThreads), lds, st, (const uint16_t*)X,
-                           (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in, d_out, col_tiles, row_tiles,
-                           groups_per_xcd);
-    } else {
-        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(k_linear<false>, dim3((unsigned)blocks), dim3(kThreads), lds, st, (const uint16_t*)X,
-                           (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in, d_out, col_tiles, row_tiles,
-                           groups_per_xcd);
+#define GTA_LAUNCH_LINEAR(KM, KS)                                                                                  \
+    do {                                                                                                           \
+        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<KM, KS>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                        (int)lds));                                                                \
+        hipLaunchKernelGGL((k_linear<KM, KS>), dim3((unsigned)blocks), dim3(kThreads), lds, st, (const uint16_t*)X, \
+                           (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in, d_out, col_tiles,        \
+                           row_tiles, groups_per_xcd);                                                             \
+    } while (0)
+#define GTA_LINEAR_BY_K(KM)                                  \
+    switch (d_in) {                                          \
+        case 64: GTA_LAUNCH_LINEAR(KM, 4); break;            \
+        case 128: GTA_LAUNCH_LINEAR(KM, 8); break;           \
+        case 256: GTA_LAUNCH_LINEAR(KM, 16); break;          \
+        default: GTA_LAUNCH_LINEAR(KM, 0); break;            \
     }
+    if (trans_w) { GTA_LINEAR_BY_K(true) } else { GTA_LINEAR_BY_K(false) }
+#undef GTA_LINEAR_BY_K
+#undef GTA_LAUNCH_LINEAR
     GTA_HIP_TRY(hipGetLastError());
     return GTA_OK;
 }
