@@ -40,10 +40,11 @@ __device__ __forceinline__ uint32_t half_of(const uint4& u, int e) {
 // Y[n, d_out] = X[n, d_in] * op(W) (+ C).  A workgroup owns one 64-column tile of op(W), staged in
 // LDS once ("k contiguous"); after that its four wavefronts never synchronise with each other.
 // Wavefront w walks over 32-row tiles of X (rows 32 w .. 32 w + 31 of the workgroup's 128-row
-// tiles).  X fragments come straight from global memory — a lane's 8 k values are 16 contiguous
-// bytes of its row — and run one full tile ahead of the arithmetic in registers.  The 32 x 64 result is
-// rounded to bf16, exchanged through a per-wavefront LDS patch and written with coalesced
-// 16-byte stores; an addend C is read the same way.
+// tiles).  The weight fragment is the MFMA's A operand and the X fragment its B operand, so the
+// accumulator holds Y transposed: a lane owns ONE row of Y (l % 32) and, per group of four
+// accumulator values, four consecutive columns — 8 bytes of the row once rounded to bf16.  The
+// 32 x 64 result goes through a per-wavefront LDS patch in 8-byte pieces and leaves in coalesced
+// 16-byte stores; an addend C comes in the same way.
 //   W_KMAJOR = true : W is stored [d_out, d_in] (Y = X W^T)   -> panel rows are copied
 //   W_KMAJOR = false: W is stored [d_in, d_out] (Y = X W)     -> panel is transposed while staged
 // Workgroups whose ids differ by 8 (same XCD) take the same row tiles for different column tiles,
@@ -52,6 +53,11 @@ constexpr int kRowsPerBlock = 128, kColsPerBlock = 64;
 constexpr int kStepsPerChunk = 8;                   // k steps (of 16) staged per chunk
 constexpr int kPatchPitch = kColsPerBlock + kPad;   // bf16 elements per row of a wavefront's 32-row result patch
 constexpr int kStagePitch = 16 * kStepsPerChunk + kPad;   // ... and of its X stage (which the patch reuses)
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 inline size_t linear_lds_bytes(int d_in) {
     return sizeof(uint16_t) * ((size_t)kColsPerBlock * (d_in + kPad) + (size_t)kRowsPerBlock * kStagePitch);
@@ -65,12 +71,19 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// KSTEPS = d_in / 16 at compile time for d_in = 64, 128, 256 (0: any d_in, read from the argument,
-// without run-ahead).  With a compile-time reduction length every load of the main loop is
-// unconditional and branch-free, which is what lets the compiler count outstanding loads exactly
-// instead of waiting for all of them before each MFMA (rows past the end are clamped to the last
-// row; their results are never stored).
-template <bool W_KMAJOR, int KSTEPS>
+// two floats -> two bf16 (round to nearest even) in one dword: v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Fast form (KSTEPS = d_in / 16 at compile time for d_in = 64, 128, 256; d_out a multiple of 64):
+// the main loop has no data-dependent branch at all.  Every load and store is unconditional —
+// rows past the end are clamped to the last row, whose values they then recompute and store once
+// more — so the compiler can count the memory operations in flight exactly and wait only for the
+// ones it needs; any guarded access inside the loop makes it wait for all of them, which ends the
+// run-ahead.  The generic form (KSTEPS = 0) takes any d_in, d_out with bounds checks and no run-ahead.
+template <bool W_KMAJOR, int KSTEPS, bool HAS_C>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const uint16_t* __restrict__ C,
          uint16_t* __restrict__ Y, int64_t n, int d_in_arg, int d_out, int col_tiles, int64_t row_tiles,
@@ -116,46 +129,34 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
     const int64_t my_tiles = first_tile < row_tiles ? (row_tiles - first_tile + tile_stride - 1) / tile_stride : 0;
     if (my_tiles == 0) return;
     auto tile_row0 = [&](int64_t m) { return (first_tile + m * tile_stride) * kRowsPerBlock + 32 * w; };
-    auto lane_src = [&](int64_t m) {   // this lane's row of tile m (clamped: such rows are computed, never stored)
-        int64_t row = tile_row0(m < my_tiles ? m : my_tiles - 1) + r32;
-        if (row >= n) row = n - 1;
-        return X + row * d_in + 8 * g;
-    };
-    floatx16 acc[2];
+    floatx16 acc[2];   // acc[t][v]: row r32, column 32 t + 8 (v / 4) + 4 g + v % 4 of the wavefront's 32 x 64 tile
+    uint16_t* my_patch = patch + r32 * kPatchPitch + 4 * g;   // this lane's 8-byte pieces: + 32 t + 8 (v / 4)
 
-    auto finish_tile = [&](int64_t m) {   // (+ C), round, exchange through the patch, coalesced stores
-        const int64_t row0 = tile_row0(m);
-        if (C) {
-            wave_lds_fence();   // the patch may still be read by this wavefront's previous stores
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {   // 32 rows x 8 units of 8 columns
-                const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
-                uint4 c = make_uint4(0, 0, 0, 0);
-                if (row0 + r < n && col0 + cu * 8 < d_out)
-                    c = *reinterpret_cast<const uint4*>(C + (row0 + r) * d_out + col0 + cu * 8);
-                *reinterpret_cast<uint4*>(patch + r * kPatchPitch + cu * 8) = c;
-            }
-            wave_lds_fence();
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    acc[t][v] += bf16_value(patch[out_row(v, lane) * kPatchPitch + 32 * t + r32]);
-        }
+    auto add_patch = [&]() {   // acc += the bf16 tile that was just written to the patch (row-major)
         wave_lds_fence();
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                patch[out_row(v, lane) * kPatchPitch + 32 * t + r32] = (uint16_t)bf16_bits(acc[t][v]);
-        wave_lds_fence();
+            for (int qd = 0; qd < 4; ++qd) {
+                const u32x2 c = *reinterpret_cast<const u32x2*>(my_patch + 32 * t + 8 * qd);
+                acc[t][4 * qd + 0] += __uint_as_float(c.x << 16);
+                acc[t][4 * qd + 1] += __uint_as_float(c.x & 0xFFFF0000u);
+                acc[t][4 * qd + 2] += __uint_as_float(c.y << 16);
+                acc[t][4 * qd + 3] += __uint_as_float(c.y & 0xFFFF0000u);
+            }
+    };
+    auto acc_to_patch = [&]() {   // round and lay the tile out row-major in the patch
+        wave_lds_fence();         // earlier reads of the patch / stage by this wavefront are issued
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
-            if (row0 + r < n && col0 + cu * 8 < d_out)
-                *reinterpret_cast<uint4*>(Y + (row0 + r) * d_out + col0 + cu * 8) =
-                    *reinterpret_cast<const uint4*>(patch + r * kPatchPitch + cu * 8);
-        }
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                u32x2 o;
+                o.x = pack_bf16x2(acc[t][4 * qd + 0], acc[t][4 * qd + 1]);
+                o.y = pack_bf16x2(acc[t][4 * qd + 2], acc[t][4 * qd + 3]);
+                *reinterpret_cast<u32x2*>(my_patch + 32 * t + 8 * qd) = o;
+            }
+        wave_lds_fence();
     };
 
     if constexpr (KSTEPS > 0) {
@@ -163,36 +164,51 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
         // up to 8 k steps (256 bytes per row).  The global loads are fully coalesced (a load
         // instruction covers 4 rows x 256 contiguous bytes = 8 whole cache lines; reading the
         // fragments directly would touch 32 lines per instruction and is bound by the L1's line
-        // rate) and run two chunks — one tile at d_in = 256 — ahead in two register sets.
+        // rate) and run two chunks — one tile at d_in = 256 — ahead in two register sets.  The
+        // addend's 32 x 64 tile travels with the chunk that completes its tile.
         constexpr int CS = KSTEPS < kStepsPerChunk ? KSTEPS : kStepsPerChunk;   // k steps per chunk
-        constexpr int CHUNKS = KSTEPS / CS;
+        constexpr int CHUNKS = KSTEPS / CS;              // 1 or 2; even steps are chunk 0 when 2
         constexpr int UNITS = CS * 2;                    // 16-byte units per row of a chunk
         constexpr int ROWS_PER_LOAD = 64 / UNITS;        // rows one load instruction covers
         constexpr int LOADS = 32 / ROWS_PER_LOAD;        // load instructions per chunk
+        static_assert(CHUNKS == 1 || CHUNKS == 2, "a tile is one or two chunks");
         const int64_t steps = my_tiles * CHUNKS;         // step s = (tile s / CHUNKS, chunk s % CHUNKS)
         const int urow = lane / UNITS, ucol = lane % UNITS;
-        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-        u32x4 set0[LOADS], set1[LOADS];   // the units of the even / odd steps (then of the step two later)
-#define GTA_FETCH(SET, STEP)                                                                   \
+        const int crow = lane >> 3, ccol = col0 + 8 * (lane & 7);   // addend / result units: 8 rows x 8 units per instruction
+        const int64_t last_row = n - 1;
+        u32x4 set0[LOADS], set1[LOADS];   // the X units of the even / odd steps (then of the step two later)
+        u32x4 cset0[4], cset1[4];         // the addend tiles that belong to them
+#define GTA_FETCH_X(SET, STEP, ODD)                                                                \
         {                                                                                          \
             int64_t fs = (STEP);                                                                   \
-            if (fs >= steps) fs = steps - 1; /* past the end: re-read the last chunk (unused) */  \
+            if (fs >= steps) fs = steps - 1; /* past the end: re-read the last tile (unused) */    \
             const int64_t frow0 = tile_row0(fs / CHUNKS);                                          \
-            const int fkc = (int)(fs % CHUNKS) * (16 * CS);                                        \
+            constexpr int fk = (CHUNKS == 1 ? 0 : (ODD)) * (16 * CS);                              \
             _Pragma("unroll") for (int q = 0; q < LOADS; ++q) {                                    \
                 int64_t row = frow0 + q * ROWS_PER_LOAD + urow;                                    \
-                if (row >= n) row = n - 1; /* clamped rows are computed but never stored */       \
-                SET[q] = *reinterpret_cast<const u32x4*>(X + row * d_in + fkc + 8 * ucol);         \
+                row = row < last_row ? row : last_row;                                             \
+                SET[q] = *reinterpret_cast<const u32x4*>(X + row * d_in + fk + 8 * ucol);          \
             }                                                                                      \
         }
-#define GTA_STEP(SET, STEP)                                                                        \
+#define GTA_FETCH_C(CSET, STEP, ODD)                                                               \
+        if constexpr (HAS_C && (CHUNKS == 1 || (ODD))) {                                           \
+            int64_t fs = (STEP);                                                                   \
+            if (fs >= steps) fs = steps - 1;                                                       \
+            const int64_t frow0 = tile_row0(fs / CHUNKS);                                          \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                        \
+                int64_t row = frow0 + 8 * q + crow;                                                \
+                row = row < last_row ? row : last_row;                                             \
+                CSET[q] = *reinterpret_cast<const u32x4*>(C + row * d_out + ccol);                 \
+            }                                                                                      \
+        }
+#define GTA_STEP(SET, CSET, STEP, ODD, AHEAD)                                                      \
         {                                                                                          \
             const int64_t s = (STEP);                                                              \
-            const int chunk = (int)(s % CHUNKS);                                                   \
+            constexpr int chunk = CHUNKS == 1 ? 0 : (ODD);                                         \
             wave_lds_fence(); /* earlier fragment / patch reads of this wavefront are issued */    \
             _Pragma("unroll") for (int q = 0; q < LOADS; ++q)                                      \
                 *reinterpret_cast<u32x4*>(stage + (q * ROWS_PER_LOAD + urow) * kStagePitch + 8 * ucol) = SET[q]; \
-            GTA_FETCH(SET, s + 2)                                                                  \
+            if (AHEAD) GTA_FETCH_X(SET, s + 2, ODD)                                                \
             __builtin_amdgcn_sched_barrier(0);                                                     \
             wave_lds_fence();                                                                      \
             if (chunk == 0) {                                                                      \
@@ -200,42 +216,85 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
                     _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;                \
             }                                                                                      \
             const uint16_t* wrow = panel + r32 * pitch + chunk * (16 * CS) + 8 * g;                \
-            const uint16_t* arow = stage + r32 * kStagePitch + 8 * g;                              \
+            const uint16_t* xrow = stage + r32 * kStagePitch + 8 * g;                              \
             _Pragma("unroll") for (int i = 0; i < CS; ++i) {                                       \
-                const uint4 a = *reinterpret_cast<const uint4*>(arow + 16 * i);                    \
-                const uint4 b0 = *reinterpret_cast<const uint4*>(wrow + 16 * i);                   \
-                const uint4 b1 = *reinterpret_cast<const uint4*>(wrow + 32 * pitch + 16 * i);      \
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(b0), acc[0], 0, 0, 0); \
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(b1), acc[1], 0, 0, 0); \
+                const uint4 xf = *reinterpret_cast<const uint4*>(xrow + 16 * i);                   \
+                const uint4 w0 = *reinterpret_cast<const uint4*>(wrow + 16 * i);                   \
+                const uint4 w1 = *reinterpret_cast<const uint4*>(wrow + 32 * pitch + 16 * i);      \
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w0), as_frag(xf), acc[0], 0, 0, 0); \
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w1), as_frag(xf), acc[1], 0, 0, 0); \
             }                                                                                      \
-            if (chunk == CHUNKS - 1) finish_tile(s / CHUNKS);                                      \
+            if (chunk == CHUNKS - 1) {                                                             \
+                const int64_t row0 = tile_row0(s / CHUNKS);                                        \
+                if constexpr (HAS_C) {                                                             \
+                    wave_lds_fence();                                                              \
+                    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                  \
+                        *reinterpret_cast<u32x4*>(patch + (8 * q + crow) * kPatchPitch + 8 * (lane & 7)) = CSET[q]; \
+                    add_patch();                                                                   \
+                }                                                                                  \
+                acc_to_patch();                                                                    \
+                _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                    \
+                    int64_t row = row0 + 8 * q + crow;                                             \
+                    row = row < last_row ? row : last_row;                                         \
+                    *reinterpret_cast<u32x4*>(Y + row * d_out + ccol) =                            \
+                        *reinterpret_cast<const u32x4*>(patch + (8 * q + crow) * kPatchPitch + 8 * (lane & 7)); \
+                }                                                                                  \
+                if (AHEAD) GTA_FETCH_C(CSET, s + 2, ODD)                                           \
+            }                                                                                      \
         }
-        GTA_FETCH(set0, 0)
-        GTA_FETCH(set1, 1)
-        for (int64_t s0 = 0; s0 < steps; s0 += 2) {
-            GTA_STEP(set0, s0)
-            if (s0 + 1 < steps) GTA_STEP(set1, s0 + 1)
+        GTA_FETCH_X(set0, 0, 0)
+        GTA_FETCH_C(cset0, 0, 0)
+        GTA_FETCH_X(set1, 1, 1)
+        GTA_FETCH_C(cset1, 1, 1)
+        int64_t s0 = 0;
+        for (; s0 + 1 < steps; s0 += 2) {
+            GTA_STEP(set0, cset0, s0, 0, true)
+            GTA_STEP(set1, cset1, s0 + 1, 1, true)
         }
+        if (s0 < steps) GTA_STEP(set0, cset0, s0, 0, false)   // an odd number of one-chunk tiles
 #undef GTA_STEP
-#undef GTA_FETCH
+#undef GTA_FETCH_C
+#undef GTA_FETCH_X
     } else {
-        // any reduction length: fragments are fetched when needed (no run-ahead)
+        // any shape: fragments are fetched when needed (no run-ahead), every access is bounds-checked
         const int ksteps = d_in / 16;
         for (int64_t m = 0; m < my_tiles; ++m) {
-            const uint16_t* src = lane_src(m);
+            const int64_t row0 = tile_row0(m);
+            int64_t row = row0 + r32;
+            if (row >= n) row = n - 1;   // computed, never stored
+            const uint16_t* src = X + row * d_in + 8 * g;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
             for (int i = 0; i < ksteps; ++i) {
-                const uint4 a = *reinterpret_cast<const uint4*>(src + 16 * i);
+                const uint4 xf = *reinterpret_cast<const uint4*>(src + 16 * i);
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const uint4 bfrag = *reinterpret_cast<const uint4*>(panel + (32 * t + r32) * pitch + 16 * i + 8 * g);
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(bfrag), acc[t], 0, 0, 0);
+                    const uint4 wf = *reinterpret_cast<const uint4*>(panel + (32 * t + r32) * pitch + 16 * i + 8 * g);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wf), as_frag(xf), acc[t], 0, 0, 0);
                 }
             }
-            finish_tile(m);
+            if (C) {
+                wave_lds_fence();   // the patch may still be read by this wavefront's previous stores
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {   // 32 rows x 8 units of 8 columns
+                    const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+                    uint4 c = make_uint4(0, 0, 0, 0);
+                    if (row0 + r < n && col0 + cu * 8 < d_out)
+                        c = *reinterpret_cast<const uint4*>(C + (row0 + r) * d_out + col0 + cu * 8);
+                    *reinterpret_cast<uint4*>(patch + r * kPatchPitch + cu * 8) = c;
+                }
+                add_patch();
+            }
+            acc_to_patch();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+                if (row0 + r < n && col0 + cu * 8 < d_out)
+                    *reinterpret_cast<uint4*>(Y + (row0 + r) * d_out + col0 + cu * 8) =
+                        *reinterpret_cast<const uint4*>(patch + r * kPatchPitch + cu * 8);
+            }
         }
     }
 }
@@ -404,23 +463,27 @@ extern "C" GTA_API gta_status gta_linear(const void* X, const void* W, const voi
     if (groups_per_xcd > max_groups) groups_per_xcd = max_groups;
     const int64_t blocks = groups_per_xcd * col_tiles * 8;
     LaunchTimer t(trans_w ? "linear_nt" : "linear_nn", n, 0, st);
-#define GTA_LAUNCH_LINEAR(KM, KS)                                                                                  \
+#define GTA_LAUNCH_LINEAR(KM, KS, HC)                                                                              \
     do {                                                                                                           \
-        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<KM, KS>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                        (int)lds));                                                                \
-        hipLaunchKernelGGL((k_linear<KM, KS>), dim3((unsigned)blocks), dim3(kThreads), lds, st, (const uint16_t*)X, \
-                           (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in, d_out, col_tiles,        \
-                           row_tiles, groups_per_xcd);                                                             \
+        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<KM, KS, HC>,                                         \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                    \
+        hipLaunchKernelGGL((k_linear<KM, KS, HC>), dim3((unsigned)blocks), dim3(kThreads), lds, st,                \
+                           (const uint16_t*)X, (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in,      \
+                           d_out, col_tiles, row_tiles, groups_per_xcd);                                           \
     } while (0)
+#define GTA_LINEAR_BY_C(KM, KS)                              \
+    if (C) GTA_LAUNCH_LINEAR(KM, KS, true); else GTA_LAUNCH_LINEAR(KM, KS, false)
 #define GTA_LINEAR_BY_K(KM)                                  \
-    switch (d_in) {                                          \
-        case 64: GTA_LAUNCH_LINEAR(KM, 4); break;            \
-        case 128: GTA_LAUNCH_LINEAR(KM, 8); break;           \
-        case 256: GTA_LAUNCH_LINEAR(KM, 16); break;          \
-        default: GTA_LAUNCH_LINEAR(KM, 0); break;            \
+    switch (fast ? d_in : 0) {                               \
+        case 64: GTA_LINEAR_BY_C(KM, 4); break;              \
+        case 128: GTA_LINEAR_BY_C(KM, 8); break;             \
+        case 256: GTA_LINEAR_BY_C(KM, 16); break;            \
+        default: GTA_LAUNCH_LINEAR(KM, 0, false); break;     \
     }
+    const bool fast = d_out % kColsPerBlock == 0;   // the branch-free form needs whole column tiles
     if (trans_w) { GTA_LINEAR_BY_K(true) } else { GTA_LINEAR_BY_K(false) }
 #undef GTA_LINEAR_BY_K
+#undef GTA_LINEAR_BY_C
 #undef GTA_LAUNCH_LINEAR
     GTA_HIP_TRY(hipGetLastError());
     return GTA_OK;
