@@ -49,18 +49,17 @@ __device__ __forceinline__ uint32_t half_of(const uint4& u, int e) {
 //   W_KMAJOR = false: W is stored [d_in, d_out] (Y = X W)     -> panel is transposed while staged
 // Workgroups whose ids differ by 8 (same XCD) take the same row tiles for different column tiles,
 // so the rows of X they all read come out of one L2.
-constexpr int kRowsPerBlock = 128, kColsPerBlock = 64;
 constexpr int kStepsPerChunk = 8;                   // k steps (of 16) staged per chunk
-constexpr int kPatchPitch = kColsPerBlock + kPad;   // bf16 elements per row of a wavefront's 32-row result patch
-constexpr int kStagePitch = 16 * kStepsPerChunk + kPad;   // ... and of its X stage (which the patch reuses)
+constexpr int kStagePitch = 16 * kStepsPerChunk + kPad;   // bf16 elements per row of a wavefront's 32-row X stage
+// (the result patch, 32 rows of up to 128 columns plus padding, reuses the stage)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-inline size_t linear_lds_bytes(int d_in) {
-    return sizeof(uint16_t) * ((size_t)kColsPerBlock * (d_in + kPad) + (size_t)kRowsPerBlock * kStagePitch);
+inline size_t linear_lds_bytes(int d_in, int cols, int waves) {
+    return sizeof(uint16_t) * ((size_t)cols * (d_in + kPad) + (size_t)(32 * waves) * kStagePitch);
 }
 
 // LDS traffic between the lanes of ONE wavefront: the hardware executes a wavefront's LDS
@@ -83,26 +82,32 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // more — so the compiler can count the memory operations in flight exactly and wait only for the
 // ones it needs; any guarded access inside the loop makes it wait for all of them, which ends the
 // run-ahead.  The generic form (KSTEPS = 0) takes any d_in, d_out with bounds checks and no run-ahead.
-template <bool W_KMAJOR, int KSTEPS, bool HAS_C>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <bool W_KMAJOR, int KSTEPS, bool HAS_C, int NT, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const uint16_t* __restrict__ C,
          uint16_t* __restrict__ Y, int64_t n, int d_in_arg, int d_out, int col_tiles, int64_t row_tiles,
          int64_t groups_per_xcd) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
+    constexpr int COLS = 32 * NT;                    // columns of Y per workgroup
+    constexpr int THREADS = 64 * WAVES, ROWS = 32 * WAVES;   // ... and rows of one of its row tiles
+    constexpr int kPatchPitch = COLS + kPad;         // bf16 elements per row of the result patch
+    constexpr int UPR = COLS / 8, RPI = 64 / UPR, NI = 32 / RPI;   // result tile: 16-byte units per row, rows per
+                                                                   // instruction, instructions per 32-row tile
+    static_assert(kPatchPitch <= kStagePitch, "the patch lives in the stage");
     const int d_in = KSTEPS > 0 ? KSTEPS * 16 : d_in_arg;
     const int pitch = d_in + kPad;
     uint16_t* panel = reinterpret_cast<uint16_t*>(lds_raw);                 // [64][d_in + kPad]
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 5, r32 = lane & 31;
-    uint16_t* stage = panel + kColsPerBlock * pitch + (32 * w) * kStagePitch;   // this wavefront's [32][kStagePitch]
+    uint16_t* stage = panel + COLS * pitch + (32 * w) * kStagePitch;   // this wavefront's [32][kStagePitch]
     uint16_t* patch = stage;                                                    // the result patch reuses it
     const int64_t b = blockIdx.x, j = b >> 3;
     const int xcd = (int)(b & 7);
-    const int col0 = (int)(j % col_tiles) * kColsPerBlock;
+    const int col0 = (int)(j % col_tiles) * COLS;
     const int64_t group = j / col_tiles;   // 0 .. groups_per_xcd-1; row tiles (group + m * groups_per_xcd) * 8 + xcd
 
     if (W_KMAJOR) {   // 16-byte units of the panel's rows, zero beyond d_out
         const int units_per_k = d_in / 8;
-        for (int u = threadIdx.x; u < kColsPerBlock * units_per_k; u += kThreads) {
+        for (int u = threadIdx.x; u < COLS * units_per_k; u += THREADS) {
             const int c = u / units_per_k, ku = u - c * units_per_k;
             uint4 val = make_uint4(0, 0, 0, 0);
             if (col0 + c < d_out) val = *reinterpret_cast<const uint4*>(W + (int64_t)(col0 + c) * d_in + ku * 8);
@@ -110,7 +115,7 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
         }
     } else {          // two k rows x 8 columns per step; consecutive lanes take consecutive k pairs
         const int pairs = d_in / 2;
-        for (int u = threadIdx.x; u < pairs * (kColsPerBlock / 8); u += kThreads) {
+        for (int u = threadIdx.x; u < pairs * (COLS / 8); u += THREADS) {
             const int cu = u / pairs, kp = u - cu * pairs;
             uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
             if (col0 + cu * 8 < d_out) {
@@ -128,14 +133,14 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
     const int64_t first_tile = group * 8 + xcd, tile_stride = groups_per_xcd * 8;
     const int64_t my_tiles = first_tile < row_tiles ? (row_tiles - first_tile + tile_stride - 1) / tile_stride : 0;
     if (my_tiles == 0) return;
-    auto tile_row0 = [&](int64_t m) { return (first_tile + m * tile_stride) * kRowsPerBlock + 32 * w; };
-    floatx16 acc[2];   // acc[t][v]: row r32, column 32 t + 8 (v / 4) + 4 g + v % 4 of the wavefront's 32 x 64 tile
+    auto tile_row0 = [&](int64_t m) { return (first_tile + m * tile_stride) * ROWS + 32 * w; };
+    floatx16 acc[NT];   // acc[t][v]: row r32, column 32 t + 8 (v / 4) + 4 g + v % 4 of the wavefront's 32 x COLS tile
     uint16_t* my_patch = patch + r32 * kPatchPitch + 4 * g;   // this lane's 8-byte pieces: + 32 t + 8 (v / 4)
 
     auto add_patch = [&]() {   // acc += the bf16 tile that was just written to the patch (row-major)
         wave_lds_fence();
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const u32x2 c = *reinterpret_cast<const u32x2*>(my_patch + 32 * t + 8 * qd);
@@ -148,7 +153,7 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
     auto acc_to_patch = [&]() {   // round and lay the tile out row-major in the patch
         wave_lds_fence();         // earlier reads of the patch / stage by this wavefront are issued
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 u32x2 o;
@@ -174,10 +179,10 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
         static_assert(CHUNKS == 1 || CHUNKS == 2, "a tile is one or two chunks");
         const int64_t steps = my_tiles * CHUNKS;         // step s = (tile s / CHUNKS, chunk s % CHUNKS)
         const int urow = lane / UNITS, ucol = lane % UNITS;
-        const int crow = lane >> 3, ccol = col0 + 8 * (lane & 7);   // addend / result units: 8 rows x 8 units per instruction
+        const int crow = lane / UPR, cunit = lane % UPR, ccol = col0 + 8 * cunit;   // addend / result units
         const int64_t last_row = n - 1;
         u32x4 set0[LOADS], set1[LOADS];   // the X units of the even / odd steps (then of the step two later)
-        u32x4 cset0[4], cset1[4];         // the addend tiles that belong to them
+        u32x4 cset0[NI], cset1[NI];       // the addend tiles that belong to them
 #define GTA_FETCH_X(SET, STEP, ODD)                                                                \
         {                                                                                          \
             int64_t fs = (STEP);                                                                   \
@@ -195,8 +200,8 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
             int64_t fs = (STEP);                                                                   \
             if (fs >= steps) fs = steps - 1;                                                       \
             const int64_t frow0 = tile_row0(fs / CHUNKS);                                          \
-            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                        \
-                int64_t row = frow0 + 8 * q + crow;                                                \
+            _Pragma("unroll") for (int q = 0; q < NI; ++q) {                                       \
+                int64_t row = frow0 + RPI * q + crow;                                              \
                 row = row < last_row ? row : last_row;                                             \
                 CSET[q] = *reinterpret_cast<const u32x4*>(C + row * d_out + ccol);                 \
             }                                                                                      \
@@ -212,32 +217,32 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
             __builtin_amdgcn_sched_barrier(0);                                                     \
             wave_lds_fence();                                                                      \
             if (chunk == 0) {                                                                      \
-                _Pragma("unroll") for (int t = 0; t < 2; ++t)                                      \
+                _Pragma("unroll") for (int t = 0; t < NT; ++t)                                     \
                     _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;                \
             }                                                                                      \
             const uint16_t* wrow = panel + r32 * pitch + chunk * (16 * CS) + 8 * g;                \
             const uint16_t* xrow = stage + r32 * kStagePitch + 8 * g;                              \
             _Pragma("unroll") for (int i = 0; i < CS; ++i) {                                       \
                 const uint4 xf = *reinterpret_cast<const uint4*>(xrow + 16 * i);                   \
-                const uint4 w0 = *reinterpret_cast<const uint4*>(wrow + 16 * i);                   \
-                const uint4 w1 = *reinterpret_cast<const uint4*>(wrow + 32 * pitch + 16 * i);      \
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w0), as_frag(xf), acc[0], 0, 0, 0); \
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w1), as_frag(xf), acc[1], 0, 0, 0); \
+                _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                   \
+                    const uint4 wf = *reinterpret_cast<const uint4*>(wrow + 32 * t * pitch + 16 * i); \
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wf), as_frag(xf), acc[t], 0, 0, 0); \
+                }                                                                                  \
             }                                                                                      \
             if (chunk == CHUNKS - 1) {                                                             \
                 const int64_t row0 = tile_row0(s / CHUNKS);                                        \
                 if constexpr (HAS_C) {                                                             \
                     wave_lds_fence();                                                              \
-                    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                  \
-                        *reinterpret_cast<u32x4*>(patch + (8 * q + crow) * kPatchPitch + 8 * (lane & 7)) = CSET[q]; \
+                    _Pragma("unroll") for (int q = 0; q < NI; ++q)                                 \
+                        *reinterpret_cast<u32x4*>(patch + (RPI * q + crow) * kPatchPitch + 8 * cunit) = CSET[q]; \
                     add_patch();                                                                   \
                 }                                                                                  \
                 acc_to_patch();                                                                    \
-                _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                    \
-                    int64_t row = row0 + 8 * q + crow;                                             \
+                _Pragma("unroll") for (int q = 0; q < NI; ++q) {                                   \
+                    int64_t row = row0 + RPI * q + crow;                                           \
                     row = row < last_row ? row : last_row;                                         \
                     *reinterpret_cast<u32x4*>(Y + row * d_out + ccol) =                            \
-                        *reinterpret_cast<const u32x4*>(patch + (8 * q + crow) * kPatchPitch + 8 * (lane & 7)); \
+                        *reinterpret_cast<const u32x4*>(patch + (RPI * q + crow) * kPatchPitch + 8 * cunit); \
                 }                                                                                  \
                 if (AHEAD) GTA_FETCH_C(CSET, s + 2, ODD)                                           \
             }                                                                                      \
@@ -264,13 +269,13 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
             if (row >= n) row = n - 1;   // computed, never stored
             const uint16_t* src = X + row * d_in + 8 * g;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
             for (int i = 0; i < ksteps; ++i) {
                 const uint4 xf = *reinterpret_cast<const uint4*>(src + 16 * i);
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
+                for (int t = 0; t < NT; ++t) {
                     const uint4 wf = *reinterpret_cast<const uint4*>(panel + (32 * t + r32) * pitch + 16 * i + 8 * g);
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wf), as_frag(xf), acc[t], 0, 0, 0);
                 }
@@ -278,8 +283,8 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
             if (C) {
                 wave_lds_fence();   // the patch may still be read by this wavefront's previous stores
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {   // 32 rows x 8 units of 8 columns
-                    const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+                for (int q = 0; q < NI; ++q) {   // 32 rows x UPR units of 8 columns
+                    const int u = lane + 64 * q, r = u / UPR, cu = u % UPR;
                     uint4 c = make_uint4(0, 0, 0, 0);
                     if (row0 + r < n && col0 + cu * 8 < d_out)
                         c = *reinterpret_cast<const uint4*>(C + (row0 + r) * d_out + col0 + cu * 8);
@@ -289,8 +294,8 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
             }
             acc_to_patch();
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int u = lane + 64 * q, r = u >> 3, cu = u & 7;
+            for (int q = 0; q < NI; ++q) {
+                const int u = lane + 64 * q, r = u / UPR, cu = u % UPR;
                 if (row0 + r < n && col0 + cu * 8 < d_out)
                     *reinterpret_cast<uint4*>(Y + (row0 + r) * d_out + col0 + cu * 8) =
                         *reinterpret_cast<const uint4*>(patch + r * kPatchPitch + cu * 8);
@@ -452,35 +457,46 @@ extern "C" GTA_API gta_status gta_linear(const void* X, const void* W, const voi
     if (!X || !W || !Y) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
     if (((uintptr_t)X & 15) || ((uintptr_t)W & 15)) return fail(GTA_ERR_INVALID_ARG, "X and W must be 16-byte aligned");
     if (((uintptr_t)Y & 15) || ((uintptr_t)C & 15)) return fail(GTA_ERR_INVALID_ARG, "Y and C must be 16-byte aligned");
-    const size_t lds = linear_lds_bytes(d_in);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int col_tiles = (d_out + kColsPerBlock - 1) / kColsPerBlock;
-    const int64_t row_tiles = (n + kRowsPerBlock - 1) / kRowsPerBlock;
-    // about 512 workgroups (2 per compute unit, what the register budget allows) in total
-    int64_t groups_per_xcd = 64 / col_tiles;
+    // Shape of a workgroup.  Every column tile of a row block re-reads the block's rows of X (out of
+    // L2), so wider column tiles mean less traffic; the weight panel of the tile has to fit in LDS
+    // next to the wavefronts' stages, with 8 wavefronts per compute unit in all (the register budget):
+    //   d_in <= 128, d_out % 128 == 0: 128 columns, 4 wavefronts, two workgroups per compute unit
+    //   d_in == 256, d_out % 128 == 0: 128 columns, 8 wavefronts, one workgroup per compute unit
+    //   otherwise                     : 64 columns, 4 wavefronts, two per compute unit
+    // The branch-free form needs whole column tiles and a compile-time d_in.
+    const bool known_k = d_in == 64 || d_in == 128 || d_in == 256;
+    const bool wide = d_out % 128 == 0 && known_k;
+    const int cols = wide ? 128 : 64;
+    const int waves = wide && d_in == 256 ? 8 : 4;
+    const bool fast = d_out % cols == 0 && known_k;
+    const size_t lds = linear_lds_bytes(d_in, cols, waves);
+    const int col_tiles = (d_out + cols - 1) / cols;
+    const int64_t row_tiles = (n + 32 * waves - 1) / (32 * waves);
+    // 8 wavefronts per compute unit in total
+    int64_t groups_per_xcd = (waves == 8 ? 32 : 64) / col_tiles;
     if (groups_per_xcd < 1) groups_per_xcd = 1;
     const int64_t max_groups = (row_tiles + 7) / 8;
     if (groups_per_xcd > max_groups) groups_per_xcd = max_groups;
     const int64_t blocks = groups_per_xcd * col_tiles * 8;
     LaunchTimer t(trans_w ? "linear_nt" : "linear_nn", n, 0, st);
-#define GTA_LAUNCH_LINEAR(KM, KS, HC)                                                                              \
+#define GTA_LAUNCH_LINEAR(KM, KS, HC, NT, WV)                                                                      \
     do {                                                                                                           \
-        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<KM, KS, HC>,                                         \
+        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear<KM, KS, HC, NT, WV>,                                 \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                    \
-        hipLaunchKernelGGL((k_linear<KM, KS, HC>), dim3((unsigned)blocks), dim3(kThreads), lds, st,                \
+        hipLaunchKernelGGL((k_linear<KM, KS, HC, NT, WV>), dim3((unsigned)blocks), dim3(64 * WV), lds, st,         \
                            (const uint16_t*)X, (const uint16_t*)W, (const uint16_t*)C, (uint16_t*)Y, n, d_in,      \
                            d_out, col_tiles, row_tiles, groups_per_xcd);                                           \
     } while (0)
-#define GTA_LINEAR_BY_C(KM, KS)                              \
-    if (C) GTA_LAUNCH_LINEAR(KM, KS, true); else GTA_LAUNCH_LINEAR(KM, KS, false)
-#define GTA_LINEAR_BY_K(KM)                                  \
-    switch (fast ? d_in : 0) {                               \
-        case 64: GTA_LINEAR_BY_C(KM, 4); break;              \
-        case 128: GTA_LINEAR_BY_C(KM, 8); break;             \
-        case 256: GTA_LINEAR_BY_C(KM, 16); break;            \
-        default: GTA_LAUNCH_LINEAR(KM, 0, false); break;     \
+#define GTA_LINEAR_BY_C(KM, KS, NT, WV)                      \
+    if (C) GTA_LAUNCH_LINEAR(KM, KS, true, NT, WV); else GTA_LAUNCH_LINEAR(KM, KS, false, NT, WV)
+#define GTA_LINEAR_BY_K(KM)                                                                                  \
+    switch (fast ? d_in : 0) {                                                                               \
+        case 64: if (wide) { GTA_LINEAR_BY_C(KM, 4, 4, 4); } else { GTA_LINEAR_BY_C(KM, 4, 2, 4); } break;   \
+        case 128: if (wide) { GTA_LINEAR_BY_C(KM, 8, 4, 4); } else { GTA_LINEAR_BY_C(KM, 8, 2, 4); } break;  \
+        case 256: if (wide) { GTA_LINEAR_BY_C(KM, 16, 4, 8); } else { GTA_LINEAR_BY_C(KM, 16, 2, 4); } break; \
+        default: GTA_LAUNCH_LINEAR(KM, 0, false, 2, 4); break;                                               \
     }
-    const bool fast = d_out % kColsPerBlock == 0;   // the branch-free form needs whole column tiles
     if (trans_w) { GTA_LINEAR_BY_K(true) } else { GTA_LINEAR_BY_K(false) }
 #undef GTA_LINEAR_BY_K
 #undef GTA_LINEAR_BY_C

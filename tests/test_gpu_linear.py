@@ -21,6 +21,8 @@ def bf16_matrix(rows, cols, seed, stream, scale=1.0):
 @pytest.mark.parametrize("n,d_in,d_out", [
     (1000, 128, 128), (4097, 256, 256), (333, 64, 64), (2048, 256, 768), (513, 128, 384), (129, 512, 512),
     (64, 16, 8), (1, 32, 40), (5000, 48, 200),
+    # enough rows that a wavefront walks over several tiles (run-ahead loop, odd and even tile counts, ragged end)
+    (150001, 128, 128), (200003, 256, 256), (140000, 256, 64), (131073, 64, 128), (197000, 128, 64),
 ])
 def test_linear_forward_forms(n, d_in, d_out):
     import paper_2604_16715_amd as gta
