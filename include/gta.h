@@ -145,6 +145,28 @@ gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32
                         int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
                         float scale, void* scratch, size_t scratch_bytes, void* stream);
 
+/* The same two calls for a GPU whose K / V rows sit in two allocations (Section 3.1, Algorithm 1:
+ * the rows it owns, and the halo rows an all-gather delivered into a receive buffer), so that no
+ * concatenated copy has to be made.  Source ids 0 .. n_local-1 address K_local / V_local
+ * [n_local, heads, head_dim], ids n_local .. n_src-1 address row (id - n_local) of K_halo / V_halo
+ * [n_src - n_local, heads, head_dim]; the backward writes dK / dV the same way (the halo part is
+ * what a reduce-scatter returns to the owners).  0 <= n_local <= n_src; the halo pointers may be
+ * NULL only when n_local == n_src.  Results are bitwise those of gta_attn_fwd / gta_attn_bwd on
+ * the concatenated tensors.  Everything else as above. */
+gta_status gta_attn_fwd_halo(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                             const void* Q, const void* K_local, const void* V_local,
+                             const void* K_halo, const void* V_halo, int64_t n_local, void* out,
+                             float* lse, int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                             gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
+                             void* stream);
+gta_status gta_attn_bwd_halo(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                             const void* Q, const void* K_local, const void* V_local,
+                             const void* K_halo, const void* V_halo, int64_t n_local, const void* out,
+                             const float* lse, const void* dOut, void* dQ, void* dK_local,
+                             void* dV_local, void* dK_halo, void* dV_halo, int64_t n_dst, int64_t n_src,
+                             int heads, int head_dim, gta_dtype dtype, float scale, void* scratch,
+                             size_t scratch_bytes, void* stream);
+
 /* ---- The same computation as separate operators (Section 2.2 counts them: forward = 1 SDDMM +
  * softmax + 1 SpMM, backward = 3 SpMM + 1 SDDMM), with the per-entry matrices stored as
  * float [nnz, heads] in the order of `indices`.  Not used by gta_attn_fwd/bwd; provided so the

@@ -159,3 +159,20 @@ def spmm(indptr, indices, W, X, n_src=None, transposed=False):
         lib.sga_spmm_t(n_dst, n_src, indptr.ctypes.data, indices.ctypes.data, H, D, W.ctypes.data, X.ctypes.data,
                        Y.ctypes.data)
     return Y
+
+
+def merge(out_a, lse_a, out_b, lse_b):
+    """Attention over the union of two disjoint sets of stored entries of the same rows, from the
+    two partial results (out [n,H,D], lse [n,H]): the softmax denominators add,
+    lse = log(exp(lse_a) + exp(lse_b)), and each partial output is re-weighted by its share
+    exp(lse_x - lse) of the total (Eq. 2 with the neighbour sum split in two).  A side whose lse is
+    -inf (no entries) contributes nothing; both -inf gives out = 0, lse = -inf.  float64."""
+    out_a, out_b = _f64(out_a), _f64(out_b)
+    lse_a, lse_b = _f64(lse_a), _f64(lse_b)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        lse = np.logaddexp(lse_a, lse_b)
+        wa = np.where(np.isneginf(lse_a), 0.0, np.exp(lse_a - lse))
+        wb = np.where(np.isneginf(lse_b), 0.0, np.exp(lse_b - lse))
+    wa = np.nan_to_num(wa, nan=0.0)
+    wb = np.nan_to_num(wb, nan=0.0)
+    return wa[..., None] * out_a + wb[..., None] * out_b, lse

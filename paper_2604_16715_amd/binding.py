@@ -77,6 +77,12 @@ def load_library():
     lib.gta_attn_bwd.restype = c_int
     lib.gta_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int,
                                  c_int, c_int, c_float, vp, c_size_t, vp]
+    lib.gta_attn_fwd_halo.restype = c_int
+    lib.gta_attn_fwd_halo.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, vp, vp, c_int64, c_int64, c_int,
+                                      c_int, c_int, c_float, vp, c_size_t, vp]
+    lib.gta_attn_bwd_halo.restype = c_int
+    lib.gta_attn_bwd_halo.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, vp, vp, vp, vp, vp, vp, vp, vp,
+                                      c_int64, c_int64, c_int, c_int, c_int, c_float, vp, c_size_t, vp]
     lib.gta_sddmm.restype = c_int
     lib.gta_sddmm.argtypes = [vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
     lib.gta_edge_softmax.restype = c_int
@@ -249,6 +255,45 @@ def gta_attn_bwd(plan: Plan, Q, K, V, out, lse, dOut, scale: float = 0.0, dQ=Non
                                        n_dst, K.shape[0], heads, head_dim, code, scale, _ptr(scratch),
                                        scratch.numel(), _stream()))
     return dQ, dK, dV
+
+
+def gta_attn_fwd_halo(plan: Plan, Q, K_local, V_local, K_halo, V_halo, scale: float = 0.0, out=None, lse=None):
+    """gta_attn_fwd with K / V given as the owned rows and a separate tensor of halo rows."""
+    n_dst, heads, head_dim = Q.shape
+    code = _dtype_code(Q)
+    n_local = K_local.shape[0]
+    n_src = n_local + (0 if K_halo is None else K_halo.shape[0])
+    if out is None:
+        out = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((n_dst, heads), dtype=torch.float32, device=Q.device)
+    scratch = plan.scratch(heads, head_dim, code)
+    _check(load_library().gta_attn_fwd_halo(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q),
+                                            _ptr(K_local), _ptr(V_local), _ptr(K_halo), _ptr(V_halo), n_local,
+                                            _ptr(out), _ptr(lse), n_dst, n_src, heads, head_dim, code, scale,
+                                            _ptr(scratch), scratch.numel(), _stream()))
+    return out, lse
+
+
+def gta_attn_bwd_halo(plan: Plan, Q, K_local, V_local, K_halo, V_halo, out, lse, dOut, scale: float = 0.0,
+                      lean_scratch: bool = False):
+    """gta_attn_bwd with K / V, dK / dV as owned rows plus halo rows; returns dQ, dK_local, dV_local,
+    dK_halo, dV_halo."""
+    n_dst, heads, head_dim = Q.shape
+    code = _dtype_code(Q)
+    n_local = K_local.shape[0]
+    n_src = n_local + (0 if K_halo is None else K_halo.shape[0])
+    dQ = torch.empty_like(Q)
+    dK_local, dV_local = torch.empty_like(K_local), torch.empty_like(V_local)
+    dK_halo = None if K_halo is None else torch.empty_like(K_halo)
+    dV_halo = None if V_halo is None else torch.empty_like(V_halo)
+    scratch = plan.scratch(heads, head_dim, code, lean_scratch)
+    _check(load_library().gta_attn_bwd_halo(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q),
+                                            _ptr(K_local), _ptr(V_local), _ptr(K_halo), _ptr(V_halo), n_local,
+                                            _ptr(out), _ptr(lse), _ptr(dOut), _ptr(dQ), _ptr(dK_local),
+                                            _ptr(dV_local), _ptr(dK_halo), _ptr(dV_halo), n_dst, n_src, heads,
+                                            head_dim, code, scale, _ptr(scratch), scratch.numel(), _stream()))
+    return dQ, dK_local, dV_local, dK_halo, dV_halo
 
 
 def gta_sddmm(plan: Plan, X, Y, Z=None):

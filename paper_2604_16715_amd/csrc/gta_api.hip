@@ -93,6 +93,7 @@ AttnArgs slice_args(const AttnArgs& a, int slice) {
     auto mvw = [off](void* p) { return p ? static_cast<void*>(static_cast<char*>(p) + off) : nullptr; };
     b.Q = mv(a.Q); b.K = mv(a.K); b.V = mv(a.V); b.out = mv(a.out); b.dO = mv(a.dO);
     b.o_out = mvw(a.o_out); b.dQ = mvw(a.dQ); b.dK = mvw(a.dK); b.dV = mvw(a.dV);
+    b.K_halo = mv(a.K_halo); b.V_halo = mv(a.V_halo); b.dK_halo = mvw(a.dK_halo); b.dV_halo = mvw(a.dV_halo);
     if (a.lse_in) b.lse_in = a.lse_in + h0;
     if (a.lse_out) b.lse_out = a.lse_out + h0;
     if (a.rowstat) b.rowstat = a.rowstat + h0;
@@ -190,17 +191,28 @@ extern "C" GTA_API size_t gta_attn_scratch_bytes_min(const gta_plan* plan, int h
     return scratch_layout(plan, sh).lean;
 }
 
-extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
-                                   const void* Q, const void* K, const void* V, void* out, float* lse,
-                                   int64_t n_dst, int64_t n_src, int heads, int head_dim,
-                                   gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
-                                   void* stream) {
+namespace {
+
+// K / V (and dK / dV) arrive either as one [n_src] tensor (halo pointers null) or as the first
+// n_local rows plus a separate tensor with the remaining n_src - n_local rows.
+gta_status check_halo(int64_t n_src, int64_t n_local, const void* a_halo, const void* b_halo) {
+    if (n_local < 0 || n_local > n_src) return fail(GTA_ERR_INVALID_ARG, "n_local must be in [0, n_src]");
+    if (n_local < n_src && (!a_halo || !b_halo)) return fail(GTA_ERR_INVALID_ARG, "null halo tensor pointer");
+    if (misaligned(a_halo) || misaligned(b_halo))
+        return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    return GTA_OK;
+}
+
+gta_status attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, const void* Q,
+                    const void* K, const void* V, const void* K_halo, const void* V_halo, int64_t n_local,
+                    void* out, float* lse, int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                    gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes, void* stream) {
     Shape sh;
     ScratchLayout sl;
     gta_status rc = check_common(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, &scale,
                                  scratch, scratch_bytes, &sh, &sl);
     if (rc != GTA_OK) return rc;
-    if ((n_dst > 0 && (!Q || !out || !lse)) || (n_src > 0 && (!K || !V)))
+    if ((n_dst > 0 && (!Q || !out || !lse)) || (n_local > 0 && (!K || !V)))
         return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(out))
         return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
@@ -208,6 +220,7 @@ extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* 
     AttnArgs a;
     memset(&a, 0, sizeof a);
     a.plan = plan; a.Q = Q; a.K = K; a.V = V; a.o_out = out; a.lse_out = lse;
+    if (n_local < n_src) { a.K_halo = K_halo; a.V_halo = V_halo; a.n_local = n_local; }
     a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
     a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
@@ -216,18 +229,17 @@ extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* 
     return GTA_OK;
 }
 
-extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
-                                   const void* Q, const void* K, const void* V, const void* out,
-                                   const float* lse, const void* dOut, void* dQ, void* dK, void* dV,
-                                   int64_t n_dst, int64_t n_src, int heads, int head_dim,
-                                   gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
-                                   void* stream) {
+gta_status attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, const void* Q,
+                    const void* K, const void* V, const void* K_halo, const void* V_halo, int64_t n_local,
+                    const void* out, const float* lse, const void* dOut, void* dQ, void* dK, void* dV,
+                    void* dK_halo, void* dV_halo, int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                    gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes, void* stream) {
     Shape sh;
     ScratchLayout sl;
     gta_status rc = check_common(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, &scale,
                                  scratch, scratch_bytes, &sh, &sl);
     if (rc != GTA_OK) return rc;
-    if ((n_dst > 0 && (!Q || !out || !lse || !dOut || !dQ)) || (n_src > 0 && (!K || !V || !dK || !dV)))
+    if ((n_dst > 0 && (!Q || !out || !lse || !dOut || !dQ)) || (n_local > 0 && (!K || !V || !dK || !dV)))
         return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(out) || misaligned(dOut) ||
         misaligned(dQ) || misaligned(dK) || misaligned(dV))
@@ -236,6 +248,9 @@ extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* 
     memset(&a, 0, sizeof a);
     a.plan = plan; a.Q = Q; a.K = K; a.V = V; a.out = out; a.dO = dOut; a.lse_in = lse;
     a.dQ = dQ; a.dK = dK; a.dV = dV;
+    if (n_local < n_src) {
+        a.K_halo = K_halo; a.V_halo = V_halo; a.dK_halo = dK_halo; a.dV_halo = dV_halo; a.n_local = n_local;
+    }
     a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
     a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
@@ -254,6 +269,54 @@ extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* 
         }
     }
     return GTA_OK;
+}
+
+}  // namespace
+
+extern "C" GTA_API gta_status gta_attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                   const void* Q, const void* K, const void* V, void* out, float* lse,
+                                   int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                                   gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
+                                   void* stream) {
+    return attn_fwd(plan, indptr, indices, Q, K, V, nullptr, nullptr, n_src, out, lse, n_dst, n_src, heads,
+                    head_dim, dtype, scale, scratch, scratch_bytes, stream);
+}
+
+extern "C" GTA_API gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                   const void* Q, const void* K, const void* V, const void* out,
+                                   const float* lse, const void* dOut, void* dQ, void* dK, void* dV,
+                                   int64_t n_dst, int64_t n_src, int heads, int head_dim,
+                                   gta_dtype dtype, float scale, void* scratch, size_t scratch_bytes,
+                                   void* stream) {
+    return attn_bwd(plan, indptr, indices, Q, K, V, nullptr, nullptr, n_src, out, lse, dOut, dQ, dK, dV,
+                    nullptr, nullptr, n_dst, n_src, heads, head_dim, dtype, scale, scratch, scratch_bytes, stream);
+}
+
+extern "C" GTA_API gta_status gta_attn_fwd_halo(const gta_plan* plan, const int64_t* indptr,
+                                        const int32_t* indices, const void* Q, const void* K_local,
+                                        const void* V_local, const void* K_halo, const void* V_halo,
+                                        int64_t n_local, void* out, float* lse, int64_t n_dst, int64_t n_src,
+                                        int heads, int head_dim, gta_dtype dtype, float scale, void* scratch,
+                                        size_t scratch_bytes, void* stream) {
+    const gta_status rc = check_halo(n_src, n_local, K_halo, V_halo);
+    if (rc != GTA_OK) return rc;
+    return attn_fwd(plan, indptr, indices, Q, K_local, V_local, K_halo, V_halo, n_local, out, lse, n_dst, n_src,
+                    heads, head_dim, dtype, scale, scratch, scratch_bytes, stream);
+}
+
+extern "C" GTA_API gta_status gta_attn_bwd_halo(const gta_plan* plan, const int64_t* indptr,
+                                        const int32_t* indices, const void* Q, const void* K_local,
+                                        const void* V_local, const void* K_halo, const void* V_halo,
+                                        int64_t n_local, const void* out, const float* lse, const void* dOut,
+                                        void* dQ, void* dK_local, void* dV_local, void* dK_halo, void* dV_halo,
+                                        int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
+                                        float scale, void* scratch, size_t scratch_bytes, void* stream) {
+    gta_status rc = check_halo(n_src, n_local, K_halo, V_halo);
+    if (rc != GTA_OK) return rc;
+    if ((rc = check_halo(n_src, n_local, dK_halo, dV_halo)) != GTA_OK) return rc;
+    return attn_bwd(plan, indptr, indices, Q, K_local, V_local, K_halo, V_halo, n_local, out, lse, dOut, dQ,
+                    dK_local, dV_local, dK_halo, dV_halo, n_dst, n_src, heads, head_dim, dtype, scale, scratch,
+                    scratch_bytes, stream);
 }
 
 extern "C" GTA_API gta_status gta_profile_enable(int on) {

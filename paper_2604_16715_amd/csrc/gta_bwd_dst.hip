@@ -22,7 +22,10 @@ struct BwdDstPass {
     static constexpr bool kUsesEntryId = false;
     static constexpr int N = NV;   // f = dQ accumulator (unscaled)
     struct Params {
-        const char *Q, *K, *V, *out, *dO;
+        const char* Q;
+        SegConst K, V;
+        int split;
+        const char *out, *dO;
         char* dQ;
         const float* lse;
         float2* rowstat;
@@ -59,8 +62,8 @@ struct BwdDstPass {
         kr[u] = make_uint4(0, 0, 0, 0);
         vr[u] = make_uint4(0, 0, 0, 0);
         if (ok) {
-            kr[u] = load16(p.K, j, p.stride, lig);
-            vr[u] = load16(p.V, j, p.stride, lig);
+            kr[u] = load16(p.K, p.split, j, p.stride, lig);
+            vr[u] = load16(p.V, p.split, j, p.stride, lig);
         }
     }
     __device__ __forceinline__ void compute(const bool (&ok)[U]) {
@@ -126,8 +129,8 @@ template <class T> gta_status run_dq(const AttnArgs& a) {
 #define GTA_CALL(LHc, Gc)                                                                            \
     {                                                                                                \
         using P = SpmmPass<T, LHc, Gc>;                                                              \
-        typename P::Params prm{a.dS, (const char*)a.K, (char*)a.dQ, a.partial, sh.row_bytes,         \
-                               a.scale, sh.heads};                                                   \
+        typename P::Params prm{a.dS, seg_of(a, a.K, a.K_halo), seg_split(a), (char*)a.dQ, a.partial, \
+                               sh.row_bytes, a.scale, sh.heads};                                     \
         return launch_pass<P>("bwd_dq", prm, a.plan, 0, a.plan->t_pos, a.stream);                                   \
     }
     GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)
@@ -140,7 +143,8 @@ template <class T> gta_status run(const AttnArgs& a) {
 #define GTA_CALL(LHc, Gc)                                                                            \
     {                                                                                                \
         using P = BwdDstPass<T, LHc, Gc>;                                                            \
-        typename P::Params prm{(const char*)a.Q, (const char*)a.K, (const char*)a.V,                 \
+        typename P::Params prm{(const char*)a.Q, seg_of(a, a.K, a.K_halo), seg_of(a, a.V, a.V_halo), \
+                               seg_split(a),                                                         \
                                (const char*)a.out, (const char*)a.dO, (char*)a.dQ, a.lse_in,         \
                                a.rowstat, a.partial, sh.row_bytes, a.scale * kLog2e, a.scale,        \
                                sh.heads};                                                            \

@@ -19,8 +19,10 @@ struct BwdSrcPass {
     static constexpr bool kUsesEntryId = STORE;
     static constexpr int N = 2 * NV;   // f = dK accumulator (unscaled), then dV accumulator
     struct Params {
-        const char *Q, *dO, *K, *V;
-        char *dK, *dV;
+        const char *Q, *dO;
+        SegConst K, V;   // read by the row that owns them
+        SegMut dK, dV;
+        int split;
         const float2* rowstat;
         float* dS;
         float* partial;
@@ -47,8 +49,8 @@ struct BwdSrcPass {
         n_heads = p.heads;
         my_lig = lig;
         if (active) {
-            kraw = load16(p.K, row, p.stride, lig);
-            vraw = load16(p.V, row, p.stride, lig);
+            kraw = load16(p.K, p.split, row, p.stride, lig);
+            vraw = load16(p.V, p.split, row, p.stride, lig);
         }
     }
     __device__ __forceinline__ void load(const Params& p, int u, int i, int e, bool ok, int lig) {
@@ -88,8 +90,8 @@ struct BwdSrcPass {
         float dk[NV], dv[NV];
 #pragma unroll
         for (int i = 0; i < NV; ++i) { dk[i] = a[i] * p.scale; dv[i] = a[NV + i]; }
-        store16(p.dK, row, p.stride, lig, Elt<T>::pack(dk));
-        store16(p.dV, row, p.stride, lig, Elt<T>::pack(dv));
+        store16(p.dK, p.split, row, p.stride, lig, Elt<T>::pack(dk));
+        store16(p.dV, p.split, row, p.stride, lig, Elt<T>::pack(dv));
     }
 };
 
@@ -98,8 +100,9 @@ template <class T, bool STORE> gta_status run(const AttnArgs& a) {
 #define GTA_CALL(LHc, Gc)                                                                         \
     {                                                                                             \
         using P = BwdSrcPass<T, LHc, Gc, STORE>;                                                  \
-        typename P::Params prm{(const char*)a.Q, (const char*)a.dO, (const char*)a.K,             \
-                               (const char*)a.V, (char*)a.dK, (char*)a.dV, a.rowstat, a.dS,       \
+        typename P::Params prm{(const char*)a.Q, (const char*)a.dO, seg_of(a, a.K, a.K_halo),     \
+                               seg_of(a, a.V, a.V_halo), seg_of(a, a.dK, a.dK_halo),              \
+                               seg_of(a, a.dV, a.dV_halo), seg_split(a), a.rowstat, a.dS,         \
                                a.partial, sh.row_bytes, a.scale * kLog2e, a.scale, sh.heads};     \
         return launch_pass<P>("bwd_src", prm, a.plan, 1, nullptr, a.stream);                               \
     }

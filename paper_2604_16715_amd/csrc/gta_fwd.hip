@@ -14,7 +14,9 @@ struct FwdPass {
     static constexpr bool kUsesEntryId = false;
     static constexpr int N = NV + 2;   // f = accumulator[NV], running max, running sum
     struct Params {
-        const char *Q, *K, *V;
+        const char* Q;
+        SegConst K, V;
+        int split;
         char* out;
         float* lse;
         float* partial;
@@ -40,8 +42,8 @@ struct FwdPass {
         kr[u] = make_uint4(0, 0, 0, 0);
         vr[u] = make_uint4(0, 0, 0, 0);
         if (ok) {
-            kr[u] = load16(p.K, j, p.stride, lig);
-            vr[u] = load16(p.V, j, p.stride, lig);
+            kr[u] = load16(p.K, p.split, j, p.stride, lig);
+            vr[u] = load16(p.V, p.split, j, p.stride, lig);
         }
     }
     __device__ __forceinline__ void compute(const bool (&ok)[U]) {
@@ -94,7 +96,8 @@ template <class T> gta_status run(const AttnArgs& a) {
 #define GTA_CALL(LHc, Gc)                                                                             \
     {                                                                                                 \
         using P = FwdPass<T, LHc, Gc>;                                                                \
-        typename P::Params prm{(const char*)a.Q, (const char*)a.K, (const char*)a.V, (char*)a.o_out,  \
+        typename P::Params prm{(const char*)a.Q, seg_of(a, a.K, a.K_halo), seg_of(a, a.V, a.V_halo),  \
+                               seg_split(a), (char*)a.o_out,                                          \
                                a.lse_out, a.partial, sh.row_bytes, a.scale * kLog2e, sh.heads};       \
         return launch_pass<P>("fwd", prm, a.plan, 0, nullptr, a.stream);                                       \
     }

@@ -94,10 +94,19 @@ struct Split {
 Split make_split(const gta_plan* plan, int side, int lanes_per_row);
 
 // arguments common to the attention launches
+// A tensor with one row per source that may live in two allocations (Algorithm 1: the rows this
+// GPU owns, then the halo rows it received): rows below the split are in `lo`, the others in
+// `hi`, which is kept pre-offset by -split rows so that both are addressed with the source id.
+struct SegConst { const char *lo, *hi; };
+struct SegMut { char *lo, *hi; };
+
 struct AttnArgs {
     const gta_plan* plan;
     const void *Q, *K, *V, *out, *dO;
     void *o_out, *dQ, *dK, *dV;
+    const void *K_halo, *V_halo;   // rows n_local .. n_src-1 of K / V when they are separate, else null
+    void *dK_halo, *dV_halo;       // ... and of dK / dV
+    int64_t n_local;               // meaningful when K_halo is set
     const float* lse_in;
     float* lse_out;
     float2* rowstat;     // [n_dst, heads] (lse * log2(e), delta)
@@ -109,6 +118,20 @@ struct AttnArgs {
 };
 
 AttnArgs slice_args(const AttnArgs& a, int slice);   // pointers moved to the slice's first head
+
+inline int seg_split(const AttnArgs& a) { return a.K_halo ? (int)a.n_local : INT32_MAX; }
+inline SegConst seg_of(const AttnArgs& a, const void* local, const void* halo) {
+    const char* lo = static_cast<const char*>(local);
+    if (!a.K_halo) return SegConst{lo, lo};
+    return SegConst{lo, reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(halo) -
+                                                      (uintptr_t)(a.n_local * a.shape.row_bytes))};
+}
+inline SegMut seg_of(const AttnArgs& a, void* local, void* halo) {
+    char* lo = static_cast<char*>(local);
+    if (!a.K_halo) return SegMut{lo, lo};
+    return SegMut{lo, reinterpret_cast<char*>(reinterpret_cast<uintptr_t>(halo) -
+                                              (uintptr_t)(a.n_local * a.shape.row_bytes))};
+}
 
 gta_status launch_fwd(const AttnArgs& a);
 gta_status launch_bwd_dst(const AttnArgs& a);

@@ -88,6 +88,13 @@ __device__ __forceinline__ uint4 load16(const char* base, int64_t row, int64_t s
 __device__ __forceinline__ void store16(char* base, int64_t row, int64_t stride, int lig, uint4 v) {
     *reinterpret_cast<uint4*>(base + row * stride + lig * 16) = v;
 }
+// rows of a two-segment source tensor
+__device__ __forceinline__ uint4 load16(const SegConst& t, int split, int row, int64_t stride, int lig) {
+    return load16(row < split ? t.lo : t.hi, row, stride, lig);
+}
+__device__ __forceinline__ void store16(const SegMut& t, int split, int row, int64_t stride, int lig, uint4 v) {
+    store16(row < split ? t.lo : t.hi, row, stride, lig, v);
+}
 
 // ---------------------------------------------------------------- cross-lane helpers
 template <int CTRL> __device__ __forceinline__ float dpp_read(float x) {

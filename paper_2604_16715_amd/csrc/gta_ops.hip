@@ -171,7 +171,8 @@ template <class T> gta_status run_spmm(const gta_plan* plan, int side, const Sha
 #define GTA_CALL(LHc, Gc)                                                                        \
     {                                                                                            \
         using P = SpmmPass<T, LHc, Gc>;                                                          \
-        typename P::Params prm{W, (const char*)X, (char*)Y, partial, sh.row_bytes, 1.0f, sh.heads};    \
+        typename P::Params prm{W, SegConst{(const char*)X, (const char*)X}, INT32_MAX, (char*)Y, partial, \
+                               sh.row_bytes, 1.0f, sh.heads};                                        \
         return launch_pass<P>(side ? "spmm_t" : "spmm", prm, plan, side, side ? plan->t_eid : nullptr, st);                    \
     }
     GTA_DISPATCH_GEOMETRY(sh.lanes_per_head, sh.lanes_per_row, GTA_CALL)

@@ -13,7 +13,8 @@ struct SpmmPass {
     static constexpr int N = NV;
     struct Params {
         const float* Wt;
-        const char* X;
+        SegConst X;   // gathered by column id
+        int split;
         char* Y;
         float* partial;
         int64_t stride;
@@ -32,7 +33,7 @@ struct SpmmPass {
         xr[u] = make_uint4(0, 0, 0, 0);
         w[u] = 0.f;
         if (ok) {
-            xr[u] = load16(p.X, j, p.stride, lig);
+            xr[u] = load16(p.X, p.split, j, p.stride, lig);
             w[u] = p.Wt[(int64_t)e * p.heads + lig / LH];
         }
     }

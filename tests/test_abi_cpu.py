@@ -61,3 +61,13 @@ def test_null_arguments_are_rejected_before_any_gpu_call(lib):
                           0, 0, 4, 16, 0, 0.0, None, 0, None)
     assert rc == 1
     assert lib.gta_plan_get_info(None, None) == 1
+    # halo forms: the split is validated before anything else
+    rc = lib.gta_attn_fwd_halo(None, None, None, None, None, None, None, None, 5, None, None, 0, 4, 4, 16, 0,
+                               0.0, None, 0, None)
+    assert rc == 1 and b"n_local" in lib.gta_last_error()
+    rc = lib.gta_attn_fwd_halo(None, None, None, None, None, None, None, None, 2, None, None, 0, 4, 4, 16, 0,
+                               0.0, None, 0, None)
+    assert rc == 1 and b"halo" in lib.gta_last_error()
+    rc = lib.gta_attn_bwd_halo(None, None, None, None, None, None, None, None, 4, None, None, None, None, None,
+                               None, None, None, 0, 4, 4, 16, 0, 0.0, None, 0, None)
+    assert rc == 1 and b"plan" in lib.gta_last_error()
