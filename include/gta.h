@@ -167,6 +167,18 @@ gta_status gta_attn_bwd_halo(const gta_plan* plan, const int64_t* indptr, const 
                              int heads, int head_dim, gta_dtype dtype, float scale, void* scratch,
                              size_t scratch_bytes, void* stream);
 
+/* Combines two forward results computed over DISJOINT sets of stored entries of the same rows
+ * (two plans over the same n_rows destinations, e.g. the entries whose sources are owned rows and
+ * the entries whose sources are halo rows of Algorithm 1, so that the first can run before the halo
+ * has arrived): per row and head, lse = log(exp(lse_a) + exp(lse_b)) and
+ * out = exp(lse_a - lse) out_a + exp(lse_b - lse) out_b, which is Eq. 2 over the union.  A side with
+ * lse = -inf contributes nothing.  out may alias out_a or out_b; lse must not alias lse_a / lse_b.
+ * The merged out and lse are what gta_attn_bwd expects when it is then called once per entry set
+ * (same Q, out, lse, dOut): the two dQ results add, dK / dV add where a source is in both sets. */
+gta_status gta_attn_merge(const void* out_a, const float* lse_a, const void* out_b, const float* lse_b,
+                          void* out, float* lse, int64_t n_rows, int heads, int head_dim,
+                          gta_dtype dtype, void* stream);
+
 /* ---- The same computation as separate operators (Section 2.2 counts them: forward = 1 SDDMM +
  * softmax + 1 SpMM, backward = 3 SpMM + 1 SDDMM), with the per-entry matrices stored as
  * float [nnz, heads] in the order of `indices`.  Not used by gta_attn_fwd/bwd; provided so the

@@ -83,6 +83,8 @@ def load_library():
     lib.gta_attn_bwd_halo.restype = c_int
     lib.gta_attn_bwd_halo.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, vp, vp, vp, vp, vp, vp, vp, vp,
                                       c_int64, c_int64, c_int, c_int, c_int, c_float, vp, c_size_t, vp]
+    lib.gta_attn_merge.restype = c_int
+    lib.gta_attn_merge.argtypes = [vp, vp, vp, vp, vp, vp, c_int64, c_int, c_int, c_int, vp]
     lib.gta_sddmm.restype = c_int
     lib.gta_sddmm.argtypes = [vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
     lib.gta_edge_softmax.restype = c_int
@@ -294,6 +296,18 @@ def gta_attn_bwd_halo(plan: Plan, Q, K_local, V_local, K_halo, V_halo, out, lse,
                                             _ptr(dV_local), _ptr(dK_halo), _ptr(dV_halo), n_dst, n_src, heads,
                                             head_dim, code, scale, _ptr(scratch), scratch.numel(), _stream()))
     return dQ, dK_local, dV_local, dK_halo, dV_halo
+
+
+def gta_attn_merge(out_a, lse_a, out_b, lse_b, out=None, lse=None):
+    """Attention over the union of two disjoint entry sets from the two partial (out, lse) results."""
+    n_rows, heads, head_dim = out_a.shape
+    if out is None:
+        out = torch.empty_like(out_a)
+    if lse is None:
+        lse = torch.empty_like(lse_a)
+    _check(load_library().gta_attn_merge(_ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b), _ptr(out), _ptr(lse),
+                                         n_rows, heads, head_dim, _dtype_code(out_a), _stream()))
+    return out, lse
 
 
 def gta_sddmm(plan: Plan, X, Y, Z=None):

@@ -1,0 +1,82 @@
+"""gta_attn_merge: attention over two disjoint entry sets, merged, against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+from helpers import TOL, Problem, assert_close, assert_lse_close, to_f64, to_torch
+
+pytestmark = pytest.mark.gpu
+
+
+def split_graph(indptr, indices, keep):
+    n = len(indptr) - 1
+    dst = np.repeat(np.arange(n), np.diff(indptr))
+    parts = []
+    for mask in (keep, ~keep):
+        cnt = np.bincount(dst[mask], minlength=n)
+        parts.append((np.concatenate([[0], np.cumsum(cnt)]).astype(np.int64), indices[mask].astype(np.int32)))
+    return parts
+
+
+@pytest.mark.parametrize("name,shrink", [("partition", 32), ("tiny", 1)])
+def test_local_then_halo_entries_merged_equal_full_attention(name, shrink):
+    import paper_2604_16715_amd as gta
+    w = gen.workload(name, shrink)
+    p = Problem.from_workload(w)
+    n_local = p.n_dst if p.n_src > p.n_dst else p.n_src // 2
+    print(f"merge case {name}/{shrink} n_src={p.n_src} n_local={n_local}", flush=True)
+    tol = TOL[p.dtype]
+    Q, K, V, dO = (to_torch(getattr(p, k)) for k in ("Q", "K", "V", "dO"))
+    parts = split_graph(p.indptr, p.indices, p.indices < n_local)   # entries with owned sources first
+    plans, partial = [], []
+    for ip, ix in parts:
+        plan = gta.gta_plan_create(torch.from_numpy(ip).cuda(), torch.from_numpy(ix).cuda(), p.n_src,
+                                   validate=True, keep_dz_min_nnz=1)
+        plans.append(plan)
+        partial.append(gta.gta_attn_fwd(plan, Q, K, V))
+    out, lse = gta.gta_attn_merge(partial[0][0], partial[0][1], partial[1][0], partial[1][1])
+    o_out, o_lse = p.oracle_forward()
+    assert_close("out", to_f64(out), o_out, tol)
+    assert_lse_close(to_f64(lse), o_lse, tol)
+    # backward once per entry set with the merged out / lse: gradients add
+    dQ = np.zeros_like(o_out)
+    dK, dV = np.zeros((p.n_src,) + o_out.shape[1:]), np.zeros((p.n_src,) + o_out.shape[1:])
+    for plan in plans:
+        g = gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO)
+        dQ += to_f64(g[0]); dK += to_f64(g[1]); dV += to_f64(g[2])
+    o_dQ, o_dK, o_dV = p.oracle_backward()
+    # the merged out was rounded once more than in a single pass, the three sums once more each
+    assert_close("dQ", dQ, o_dQ, 2 * tol)
+    assert_close("dK", dK, o_dK, 2 * tol)
+    assert_close("dV", dV, o_dV, 2 * tol)
+
+
+@pytest.mark.parametrize("n,heads,head_dim,dtype", [
+    (1000, 8, 32, "bf16"), (777, 4, 16, "f32"), (513, 2, 4, "bf16"), (300, 3, 12, "f32"), (64, 1, 64, "bf16"),
+    (129, 64, 8, "bf16"), (1, 4, 4, "f32"),
+])
+def test_merge_against_oracle_including_empty_sides(n, heads, head_dim, dtype):
+    import paper_2604_16715_amd as gta
+    print(f"merge shapes n={n} heads={heads} head_dim={head_dim} {dtype}", flush=True)
+    oa = gen.normal((n, heads, head_dim), dtype, 31, 1)
+    ob = gen.normal((n, heads, head_dim), dtype, 31, 2)
+    rng = np.random.Generator(np.random.Philox(n + heads))
+    la = (4.0 * rng.standard_normal((n, heads))).astype(np.float32)
+    lb = (4.0 * rng.standard_normal((n, heads))).astype(np.float32)
+    la[rng.random((n, heads)) < 0.15] = -np.inf      # rows / heads without entries on one side ...
+    lb[rng.random((n, heads)) < 0.15] = -np.inf      # ... or on both
+    la[0, 0] = 80.0; lb[0, 0] = -70.0                # far apart: no overflow, b's share underflows
+    ref_out, ref_lse = oracle.merge(gen.as_f32(oa).astype(np.float64), la, gen.as_f32(ob).astype(np.float64), lb)
+    ta, tb = to_torch(oa), to_torch(ob)
+    out, lse = gta.gta_attn_merge(ta, torch.from_numpy(la).cuda(), tb, torch.from_numpy(lb).cuda())
+    torch.cuda.synchronize()
+    assert_close("out", to_f64(out), ref_out, TOL[dtype])
+    assert_lse_close(to_f64(lse), ref_lse, TOL[dtype])
+    both_empty = np.isneginf(la) & np.isneginf(lb)
+    assert np.all(to_f64(out)[both_empty] == 0.0)
+    # in place over the first input
+    out2, _ = gta.gta_attn_merge(ta, torch.from_numpy(la).cuda(), tb, torch.from_numpy(lb).cuda(), out=ta)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out)
