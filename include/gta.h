@@ -26,8 +26,8 @@
  * lse: float [n_dst, heads], natural-log sum of exp of the scaled scores.  Accumulation is
  * always fp32; bf16 outputs are rounded to nearest even.
  *
- * Supported shapes: head_dim * sizeof(element) in {16, 32, 64, 128, 256} bytes; n_dst, n_src,
- * nnz < 2^31.  A row is processed slice_heads heads at a time, slice_heads being the largest power
+ * Supported shapes: head_dim * sizeof(element) in {16, 32, 64, 128, 256} bytes; n_dst, n_src
+ * < 2^31, nnz <= 2^31 - 1024.  A row is processed slice_heads heads at a time, slice_heads being the largest power
  * of two that divides `heads` and keeps a slice within 1024 bytes; a slice must span at least
  * 64 bytes.  Power-of-two head counts with rows up to 1024 bytes run in one launch per pass (the
  * tuned case); wider rows and other head counts take one launch per slice.

@@ -246,6 +246,10 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline dim3 grid_for(int64_t n, int threads) { return dim3((unsigned)std::max<int64_t>(1, ceil_div(n, threads))); }
 
+// Entry positions are 32-bit in the kernels, whose loops step past a row's end by up to one
+// workgroup's stride (256) before they stop: keep that sum representable.
+constexpr int64_t kMaxNnz = (1ll << 31) - 1024;
+
 struct Opts { int pack, wave, chunk, validate; int64_t keep_dz; };
 
 bool resolve_opts(const gta_plan_opts* o, Opts* r) {
@@ -409,7 +413,7 @@ extern "C" GTA_API size_t gta_plan_workspace_bytes(int64_t n_dst, int64_t n_src,
                                            const gta_plan_opts* opts) {
     Opts o;
     if (n_dst < 0 || n_src < 0 || nnz < 0 || n_dst >= (1ll << 31) || n_src >= (1ll << 31) ||
-        nnz >= (1ll << 31) || !resolve_opts(opts, &o))
+        nnz > kMaxNnz || !resolve_opts(opts, &o))
         return 0;
     Layout L;
     make_layout(n_dst, n_src, nnz, o, &L);
@@ -425,8 +429,8 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
     if (!indptr || (!indices && nnz > 0) || !workspace)
         return fail(GTA_ERR_INVALID_ARG, "null pointer argument");
     if (n_dst < 0 || n_src < 0 || nnz < 0) return fail(GTA_ERR_INVALID_ARG, "negative size");
-    if (n_dst >= (1ll << 31) || n_src >= (1ll << 31) || nnz >= (1ll << 31))
-        return fail(GTA_ERR_UNSUPPORTED, "n_dst, n_src and nnz must be below 2^31");
+    if (n_dst >= (1ll << 31) || n_src >= (1ll << 31) || nnz > kMaxNnz)
+        return fail(GTA_ERR_UNSUPPORTED, "n_dst and n_src must be below 2^31, nnz at most 2^31 - 1024");
     if (n_src < n_dst) return fail(GTA_ERR_INVALID_ARG, "n_src must be >= n_dst (owned rows come first)");
     Opts o;
     if (!resolve_opts(opts, &o))

@@ -40,6 +40,8 @@ def test_workspace_query_is_host_only(lib):
     assert lib.gta_plan_workspace_bytes(1000, 1500, 20000, None) > 20000 * 8
     assert lib.gta_plan_workspace_bytes(-1, 10, 10, None) == 0
     assert lib.gta_plan_workspace_bytes(10, 10, 1 << 31, None) == 0
+    assert lib.gta_plan_workspace_bytes(10, 10, (1 << 31) - 1023, None) == 0   # 32-bit positions + loop strides
+    assert lib.gta_plan_workspace_bytes(10, 10, (1 << 31) - 1024, None) > 0
     bad = _PlanOpts(0, 48, 0, 0, 0)         # not a power of two
     assert lib.gta_plan_workspace_bytes(10, 10, 10, ctypes.byref(bad)) == 0
     bad = _PlanOpts(0, 512, 256, 0, 0)      # hub_chunk < wave_max_deg
