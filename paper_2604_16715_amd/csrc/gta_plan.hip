@@ -202,18 +202,20 @@ __global__ void k_lower_bounds(const uint32_t* sorted, int64_t nnz, int64_t n_sr
     t_indptr[j] = lo;
 }
 
-// destination row of each transposed entry: the row i with indptr[i] <= eid < indptr[i+1]
-__global__ void k_row_of_entry(const int64_t* indptr, int64_t n_dst, const int32_t* t_eid,
-                               int64_t nnz, int32_t* t_indices) {
+// destination row of every stored position: one wavefront per row writes the row id over the
+// row's positions (coalesced) ...
+__global__ void __launch_bounds__(256)
+k_expand_rows(const int64_t* indptr, int64_t n_dst, int32_t* row_of_pos) {
+    const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    if (row >= n_dst) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t b = indptr[row], e = indptr[row + 1];
+    for (int64_t x = b + lane; x < e; x += 64) row_of_pos[x] = (int32_t)row;
+}
+// ... and each transposed entry picks up the row of its stored position
+__global__ void k_row_of_entry(const int32_t* row_of_pos, const int32_t* t_eid, int64_t nnz, int32_t* t_indices) {
     int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= nnz) return;
-    const int64_t e = t_eid[p];
-    int64_t lo = 0, hi = n_dst + 1;   // first index with indptr[idx] > e
-    while (lo < hi) {
-        int64_t mid = (lo + hi) >> 1;
-        if (indptr[mid] <= e) lo = mid + 1; else hi = mid;
-    }
-    t_indices[p] = (int32_t)(lo - 1);
+    if (p < nnz) t_indices[p] = row_of_pos[t_eid[p]];
 }
 
 // ------------------------------------------------------------------ chunk tables
@@ -489,8 +491,11 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
         hipLaunchKernelGGL(k_lower_bounds, grid_for(n_src + 1, 256), dim3(256), 0, b.st, ks, nnz, n_src, p->t_indptr);
         if (nnz > 0) {
             GTA_HIP_TRY(hipMemcpyAsync(p->t_eid, vs, sizeof(int32_t) * (size_t)nnz, hipMemcpyDeviceToDevice, b.st));
-            hipLaunchKernelGGL(k_row_of_entry, grid_for(nnz, 256), dim3(256), 0, b.st, indptr, n_dst,
-                               p->t_eid, nnz, p->t_indices);
+            // the sort's other value buffer is free now: it holds the row of every stored position
+            int32_t* row_of_pos = vs == b.at<int32_t>(b.L.val_a) ? b.at<int32_t>(b.L.val_b) : b.at<int32_t>(b.L.val_a);
+            hipLaunchKernelGGL(k_expand_rows, grid_for(n_dst * 64, 256), dim3(256), 0, b.st, indptr, n_dst, row_of_pos);
+            hipLaunchKernelGGL(k_row_of_entry, grid_for(nnz, 256), dim3(256), 0, b.st, row_of_pos, p->t_eid, nnz,
+                               p->t_indices);
             hipLaunchKernelGGL(k_invert, grid_for(nnz, 256), dim3(256), 0, b.st, p->t_eid, p->t_pos, nnz);
         }
         GTA_HIP_TRY(hipGetLastError());
