@@ -206,7 +206,8 @@ gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* 
  * Eq. 5: X' = X W_o + Y) and their gradients.  bfloat16 operands, fp32 accumulation; row-major,
  * contiguous, 16-byte aligned.  d_in (the reduction length) must be a multiple of 16 and at most
  * 512 for gta_linear, d_out a multiple of 8.
- * gta_linear:    Y[n, d_out] = X[n, d_in] * op(W) (+ C)      C [n, d_out] may be NULL
+ * gta_linear:    Y[n, d_out] = X[n, d_in] * op(W) (+ C)      C [n, d_out] may be NULL, and may be Y
+ *                itself (in-place accumulation: every element of C is read before it is written)
  *                trans_w = 0: W is [d_in, d_out] (Y = X W);   trans_w = 1: W is [d_out, d_in] (Y = X W^T,
  *                the form of dX = dY W^T).
  * gta_linear_dw: dW[d_in, d_out] (float) = X^T dY, X [n, d_in], dY [n, d_out]; row blocks are summed

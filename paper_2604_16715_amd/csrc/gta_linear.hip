@@ -131,9 +131,14 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
 
     // 32-row tiles of this wavefront: rows 32 w .. of the 128-row tiles (group + m * groups_per_xcd) * 8 + xcd
     const int64_t first_tile = group * 8 + xcd, tile_stride = groups_per_xcd * 8;
-    const int64_t my_tiles = first_tile < row_tiles ? (row_tiles - first_tile + tile_stride - 1) / tile_stride : 0;
-    if (my_tiles == 0) return;
     auto tile_row0 = [&](int64_t m) { return (first_tile + m * tile_stride) * ROWS + 32 * w; };
+    int64_t my_tiles = first_tile < row_tiles ? (row_tiles - first_tile + tile_stride - 1) / tile_stride : 0;
+    // A wavefront whose 32 rows of the last row block all lie past the end skips that tile: with
+    // clamped rows it would recompute row n - 1 and, when Y aliases C, could read an addend that
+    // the row's owner has already updated.  (Rows past the end INSIDE a tile are harmless: their
+    // addend loads and stores go with the owner's, in the same instructions' order.)
+    if (my_tiles > 0 && tile_row0(my_tiles - 1) >= n) --my_tiles;
+    if (my_tiles == 0) return;
     floatx16 acc[NT];   // acc[t][v]: row r32, column 32 t + 8 (v / 4) + 4 g + v % 4 of the wavefront's 32 x COLS tile
     uint16_t* my_patch = patch + r32 * kPatchPitch + 4 * g;   // this lane's 8-byte pieces: + 32 t + 8 (v / 4)
 

@@ -62,3 +62,22 @@ def test_linear_rejects_unsupported():
     W = torch.zeros((32, 16), dtype=torch.float32, device="cuda")
     with pytest.raises(gta.GtaError):
         gta.gta_linear(X, W)                     # fp32 not implemented for the projections
+
+
+@pytest.mark.parametrize("n,d", [(257, 256), (1025, 256), (70001, 256), (129, 128), (66000 + 33, 128), (130, 64), (5, 48)])
+def test_linear_accumulates_in_place(n, d):
+    """Y may alias C (dX += dY W^T in the layer's backward).  n is chosen so that whole wavefronts of the
+    last row block lie past the end: they must not touch the last row."""
+    import paper_2604_16715_amd as gta
+    print(f"linear in-place case n={n} d={d}", flush=True)
+    X, W, C = bf16_matrix(n, d, 3, 2), bf16_matrix(d, d, 3, 3, 0.125), bf16_matrix(n, d, 3, 4)
+    Xd, Wd = to_torch(X), to_torch(W)
+    for trans in (False, True):
+        ref = gta.gta_linear(Xd, Wd, to_torch(C), trans_w=trans)
+        for _ in range(3):
+            acc = to_torch(C)
+            out = gta.gta_linear(Xd, Wd, acc, trans_w=trans, Y=acc)
+            torch.cuda.synchronize()
+            assert out.data_ptr() == acc.data_ptr()
+            assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+
