@@ -37,13 +37,13 @@ __device__ __forceinline__ uint32_t half_of(const uint4& u, int e) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Y[n, d_out] = X[n, d_in] * op(W) (+ C).  A workgroup owns one 64-column tile of op(W), staged in
-// LDS once ("k contiguous"); after that its four wavefronts never synchronise with each other.
-// Wavefront w walks over 32-row tiles of X (rows 32 w .. 32 w + 31 of the workgroup's 128-row
-// tiles).  The weight fragment is the MFMA's A operand and the X fragment its B operand, so the
+// Y[n, d_out] = X[n, d_in] * op(W) (+ C).  A workgroup owns one column tile of op(W) (COLS = 64 or
+// 128 columns, template argument NT = COLS / 32), staged in LDS once ("k contiguous"); after that
+// its WAVES (4 or 8) wavefronts never synchronise with each other.  Wavefront w walks over 32-row
+// tiles of X (rows 32 w .. 32 w + 31 of the workgroup's 32 WAVES-row tiles).  The weight fragment is the MFMA's A operand and the X fragment its B operand, so the
 // accumulator holds Y transposed: a lane owns ONE row of Y (l % 32) and, per group of four
 // accumulator values, four consecutive columns — 8 bytes of the row once rounded to bf16.  The
-// 32 x 64 result goes through a per-wavefront LDS patch in 8-byte pieces and leaves in coalesced
+// 32 x COLS result goes through a per-wavefront LDS patch in 8-byte pieces and leaves in coalesced
 // 16-byte stores; an addend C comes in the same way.
 //   W_KMAJOR = true : W is stored [d_out, d_in] (Y = X W^T)   -> panel rows are copied
 //   W_KMAJOR = false: W is stored [d_in, d_out] (Y = X W)     -> panel is transposed while staged
