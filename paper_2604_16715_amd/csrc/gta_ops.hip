@@ -104,14 +104,22 @@ template <int TEAM> struct TeamReduce {
     }
 };
 
+// Both kernels keep a thread's first kSoftmaxHeld values in registers: the loads are issued
+// together (one memory latency instead of one per value) and rows of up to kSoftmaxHeld * TEAM
+// values — almost all of them — are read once; only longer rows loop and re-read.
+constexpr int kSoftmaxHeld = 8;
+constexpr int64_t kSoftmaxMaxBlocks = 256 * 32;   // workgroups walk over rows: launching one per few rows costs more than the rows
+
 template <int TEAM>
 __global__ void __launch_bounds__(kBlockThreads)
 k_edge_softmax(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64_t row_end, int H,
                float scale2, const float* Z, float* U, float* lse) {
     __shared__ float lds[kBlockThreads * 2];
-    const int64_t team = ((int64_t)blockIdx.x * kBlockThreads + threadIdx.x) / TEAM;
+    constexpr int kTeams = kBlockThreads / TEAM;
     const int t = threadIdx.x % TEAM;
-    const int64_t r = row_begin + team;
+    // a workgroup walks over rows with the grid's stride; the trip count is uniform over the workgroup
+    for (int64_t base = row_begin + (int64_t)blockIdx.x * kTeams; base < row_end; base += (int64_t)gridDim.x * kTeams) {
+    const int64_t r = base + threadIdx.x / TEAM;
     const bool active = r < row_end;   // uniform over the team (and over the block when TEAM == block)
     int64_t b = 0, e = 0;
     int row = 0;
@@ -120,8 +128,17 @@ k_edge_softmax(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64
         b = ptr[row] * H;
         e = ptr[row + 1] * H;
     }
+    float held[kSoftmaxHeld];
     float m = kNegBig, l = 0.f;
-    for (int64_t x = b + t; x < e; x += TEAM) {
+#pragma unroll
+    for (int k = 0; k < kSoftmaxHeld; ++k) {
+        const int64_t x = b + t + (int64_t)k * TEAM;
+        held[k] = x < e ? Z[x] * scale2 : -INFINITY;
+        m = fmaxf(m, held[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < kSoftmaxHeld; ++k) l += fast_exp2(held[k] - m);   // exp2(-inf) = 0 for the slots past the end
+    for (int64_t x = b + t + (int64_t)kSoftmaxHeld * TEAM; x < e; x += TEAM) {
         const float s = Z[x] * scale2;
         const float mn = fmaxf(m, s);
         l = l * fast_exp2(m - mn) + fast_exp2(s - mn);
@@ -129,8 +146,14 @@ k_edge_softmax(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64
     }
     TeamReduce<TEAM>::softmax(m, l, H, lds);
     const float lse2 = m + fast_log2(l);
-    for (int64_t x = b + t; x < e; x += TEAM) U[x] = fast_exp2(Z[x] * scale2 - lse2);
+#pragma unroll
+    for (int k = 0; k < kSoftmaxHeld; ++k) {
+        const int64_t x = b + t + (int64_t)k * TEAM;
+        if (x < e) U[x] = fast_exp2(held[k] - lse2);
+    }
+    for (int64_t x = b + t + (int64_t)kSoftmaxHeld * TEAM; x < e; x += TEAM) U[x] = fast_exp2(Z[x] * scale2 - lse2);
     if (active && lse && t < H) lse[(int64_t)row * H + t] = e > b ? lse2 * kLn2 : -INFINITY;
+    }
 }
 
 template <int TEAM>
@@ -138,19 +161,35 @@ __global__ void __launch_bounds__(kBlockThreads)
 k_edge_softmax_bwd(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64_t row_end, int H,
                    float scale, const float* U, const float* dU, float* dZ) {
     __shared__ float lds[kBlockThreads * 2];
-    const int64_t team = ((int64_t)blockIdx.x * kBlockThreads + threadIdx.x) / TEAM;
+    constexpr int kTeams = kBlockThreads / TEAM;
     const int t = threadIdx.x % TEAM;
-    const int64_t r = row_begin + team;
+    for (int64_t base = row_begin + (int64_t)blockIdx.x * kTeams; base < row_end; base += (int64_t)gridDim.x * kTeams) {
+    const int64_t r = base + threadIdx.x / TEAM;
     int64_t b = 0, e = 0;
     if (r < row_end) {
         const int row = rows[r];
         b = ptr[row] * H;
         e = ptr[row + 1] * H;
     }
+    float hu[kSoftmaxHeld], hd[kSoftmaxHeld];
     float dot = 0.f;
-    for (int64_t x = b + t; x < e; x += TEAM) dot = fmaf(U[x], dU[x], dot);
+#pragma unroll
+    for (int k = 0; k < kSoftmaxHeld; ++k) {
+        const int64_t x = b + t + (int64_t)k * TEAM;
+        hu[k] = x < e ? U[x] : 0.f;
+        hd[k] = x < e ? dU[x] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < kSoftmaxHeld; ++k) dot = fmaf(hu[k], hd[k], dot);
+    for (int64_t x = b + t + (int64_t)kSoftmaxHeld * TEAM; x < e; x += TEAM) dot = fmaf(U[x], dU[x], dot);
     dot = TeamReduce<TEAM>::sum(dot, H, lds);
-    for (int64_t x = b + t; x < e; x += TEAM) dZ[x] = scale * U[x] * (dU[x] - dot);
+#pragma unroll
+    for (int k = 0; k < kSoftmaxHeld; ++k) {
+        const int64_t x = b + t + (int64_t)k * TEAM;
+        if (x < e) dZ[x] = scale * hu[k] * (hd[k] - dot);
+    }
+    for (int64_t x = b + t + (int64_t)kSoftmaxHeld * TEAM; x < e; x += TEAM) dZ[x] = scale * U[x] * (dU[x] - dot);
+    }
 }
 
 template <class T> gta_status run_sddmm(const gta_plan* plan, const Shape& sh, const void* X, const void* Y,
@@ -290,7 +329,7 @@ extern "C" GTA_API gta_status gta_edge_softmax(const gta_plan* plan, const int64
     const Side& sd = plan->side[0];
     LaunchTimer t("edge_softmax", sd.n_rows, plan->nnz, st);
     return softmax_launches(plan, heads, "edge_softmax", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
-        hipLaunchKernelGGL(k_edge_softmax<decltype(team)::value>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st,
+        hipLaunchKernelGGL(k_edge_softmax<decltype(team)::value>, dim3((unsigned)std::min<int64_t>(blocks, kSoftmaxMaxBlocks)), dim3(kBlockThreads), 0, st,
                            sd.ptr, sd.bin_rows, rb, re, heads, scale * kLog2e, Z, U, lse);
     });
 }
@@ -307,7 +346,7 @@ extern "C" GTA_API gta_status gta_edge_softmax_bwd(const gta_plan* plan, const i
     const Side& sd = plan->side[0];
     LaunchTimer t("edge_softmax_bwd", sd.n_rows, plan->nnz, st);
     return softmax_launches(plan, heads, "edge_softmax_bwd", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
-        hipLaunchKernelGGL(k_edge_softmax_bwd<decltype(team)::value>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, st,
+        hipLaunchKernelGGL(k_edge_softmax_bwd<decltype(team)::value>, dim3((unsigned)std::min<int64_t>(blocks, kSoftmaxMaxBlocks)), dim3(kBlockThreads), 0, st,
                            sd.ptr, sd.bin_rows, rb, re, heads, scale, U, dU, dZ);
     });
 }
