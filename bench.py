@@ -138,13 +138,18 @@ def time_unfused(gta, torch, plan, Q, K, V, dO, w, steps, log) -> dict:
 def time_layer(gta, torch, plan, w, steps, log) -> dict:
     """One Sparse Graph Attention layer (Eq. 3-5), forward + backward: X' = X W_o + attention(X W_Q, X W_K, X W_V)."""
     import gen
-    if w.dtype != "bf16" or w.n_src != w.n_dst:
-        return {"skipped": "the layer form needs a bf16 workload with n_src == n_dst"}
+    if w.n_src != w.n_dst:
+        return {"skipped": "the layer form needs a workload with n_src == n_dst"}
     n, d = w.n_dst, w.heads * w.head_dim
     dev = plan.indptr.device
-    mk = lambda shape, stream: torch.from_numpy(gen.normal(shape, "bf16", w.seed, stream).view(np.int16)).to(dev).view(torch.bfloat16)
+    if w.dtype == "bf16":
+        mk = lambda shape, stream: torch.from_numpy(gen.normal(shape, "bf16", w.seed, stream).view(np.int16)).to(dev).view(torch.bfloat16)
+        tdtype, el = torch.bfloat16, 2
+    else:
+        mk = lambda shape, stream: torch.from_numpy(gen.normal(shape, "f32", w.seed, stream)).to(dev)
+        tdtype, el = torch.float32, 4
     X, dXout = mk((n, d), STREAM_X), mk((n, d), STREAM_DX)
-    Ws = [(mk((d, d), 10 + k).float() * (1.0 / float(np.sqrt(d)))).to(torch.bfloat16) for k in range(4)]
+    Ws = [(mk((d, d), 10 + k).float() * (1.0 / float(np.sqrt(d)))).to(tdtype) for k in range(4)]
 
     def step():
         _, saved = gta.gta_sga_layer_fwd(plan, X, *Ws, w.heads)
@@ -169,7 +174,7 @@ def time_layer(gta, torch, plan, w, steps, log) -> dict:
         k["ms"] += r["ms"]
         k["calls"] += 1
     flops = 2.0 * n * d * d
-    dense_bytes = {"linear_nn": n * d * 2 * 2, "linear_nt": n * d * 2 * 2, "linear_dw": n * d * 2 * 2}
+    dense_bytes = {"linear_nn": n * d * el * 2, "linear_nt": n * d * el * 2, "linear_dw": n * d * el * 2}
     ops = {}
     dense_ms = 0.0
     for name, k in agg.items():

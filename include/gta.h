@@ -203,9 +203,10 @@ gta_status gta_spmm(const gta_plan* plan, const int64_t* indptr, const int32_t* 
                     gta_dtype dtype, int transposed, void* scratch, size_t scratch_bytes, void* stream);
 
 /* ---- Dense projections of the layer on the matrix cores (Eq. 3: Q,K,V = X W_Q, X W_K, X W_V;
- * Eq. 5: X' = X W_o + Y) and their gradients.  bfloat16 operands, fp32 accumulation; row-major,
- * contiguous, 16-byte aligned.  d_in (the reduction length) must be a multiple of 16 and at most
- * 512 for gta_linear, d_out a multiple of 8.
+ * Eq. 5: X' = X W_o + Y) and their gradients.  bfloat16 or fp32 operands (all tensors of a call in
+ * the same type), fp32 accumulation; row-major, contiguous, 16-byte aligned.  d_in (the reduction
+ * length) must be a multiple of 16 and at most 512 (bfloat16) / 496 (fp32) for gta_linear, d_out a
+ * multiple of 8.
  * gta_linear:    Y[n, d_out] = X[n, d_in] * op(W) (+ C)      C [n, d_out] may be NULL, and may be Y
  *                itself (in-place accumulation: every element of C is read before it is written)
  *                trans_w = 0: W is [d_in, d_out] (Y = X W);   trans_w = 1: W is [d_out, d_in] (Y = X W^T,
@@ -218,12 +219,12 @@ size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d_out);
 gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in, int d_out,
                          gta_dtype dtype, void* scratch, size_t scratch_bytes, void* stream);
 
-/* ---- One Sparse Graph Attention layer (Eq. 3-5) on one GPU with n_src == n_dst == n, bfloat16:
+/* ---- One Sparse Graph Attention layer (Eq. 3-5) on one GPU with n_src == n_dst == n, bfloat16 or fp32:
  *   Q,K,V = X W_Q, X W_K, X W_V;   Y = attention(Q,K,V);   X' = X W_o + Y.
  * X, Q, K, V, Y, X' are [n, d] = [n, heads, head_dim]; weights are [d, d] (input x output).
  * Forward writes Q, K, V, Y, lse (kept for the backward) and Xout.  Backward takes dXout and writes
  * dX [n, d], the weight gradients dW_* (float [d, d]) and uses dQ, dK, dV [n, d] as work buffers.
- * dX accumulates four products through bfloat16 (rounded after each).  scratch:
+ * dX accumulates four products through the tensor type (rounded after each).  scratch:
  * gta_sga_layer_scratch_bytes.  Host-side sequencing of the entry points above.                  */
 size_t gta_sga_layer_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
 gta_status gta_sga_layer_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,

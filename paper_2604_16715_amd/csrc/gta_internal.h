@@ -139,4 +139,10 @@ gta_status launch_bwd_src(const AttnArgs& a);   // stores dS when a.dS is set
 gta_status launch_rowstat(const AttnArgs& a);   // (lse * log2 e, dY_i . Y_i) per (row, head)
 gta_status launch_bwd_dq(const AttnArgs& a);    // dQ = scale * dS K over the stored dS
 
+// fp32 forms of the dense projections (the bf16 forms live with their entry points)
+gta_status launch_linear_f32(const float* X, const float* W, const float* C, float* Y, int64_t n, int d_in,
+                             int d_out, int trans_w, hipStream_t st);
+void launch_linear_dw_f32(const float* X, const float* dY, float* partial, int64_t n, int d_in, int d_out,
+                          int64_t rows_per_split, int tiles_i, int tiles_o, int splits, hipStream_t st);
+
 }  // namespace gta

@@ -15,7 +15,7 @@ gta_status check_layer(const gta_plan* plan, int64_t n, int heads, int head_dim,
     if (plan->n_dst != n || plan->n_src != n)
         return fail(GTA_ERR_INVALID_ARG, "the layer form needs n_src == n_dst == n (plan has %lld, %lld)",
                     (long long)plan->n_dst, (long long)plan->n_src);
-    if (dtype != GTA_BF16) return fail(GTA_ERR_UNSUPPORTED, "the layer form is implemented for bfloat16 only");
+    if (dtype != GTA_BF16 && dtype != GTA_F32) return fail(GTA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
     if (heads <= 0 || head_dim <= 0) return fail(GTA_ERR_INVALID_ARG, "heads and head_dim must be positive");
     return GTA_OK;
 }

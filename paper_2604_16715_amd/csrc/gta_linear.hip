@@ -413,12 +413,25 @@ k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, flo
         }
 }
 
-__global__ void k_reduce_partials(const float* __restrict__ partial, float* __restrict__ dW, int64_t elems, int splits) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= elems) return;
+// Sums the row splits' partial results in a fixed order: a workgroup takes 32 consecutive elements;
+// thread (element e, group j of 8) adds splits j, j + 8, ... and the 8 group sums are then added in
+// group order.
+__global__ void __launch_bounds__(256)
+k_reduce_partials(const float* __restrict__ partial, float* __restrict__ dW, int64_t elems, int splits) {
+    __shared__ float part[8][32];
+    const int e = threadIdx.x & 31, j = threadIdx.x >> 5;
+    const int64_t i = (int64_t)blockIdx.x * 32 + e;
     float acc = 0.f;
-    for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * elems + i];
-    dW[i] = acc;
+    if (i < elems)
+        for (int s = j; s < splits; s += 8) acc += partial[(int64_t)s * elems + i];
+    part[j][e] = acc;
+    __syncthreads();
+    if (j == 0 && i < elems) {
+        float total = part[0][e];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) total += part[k][e];
+        dW[i] = total;
+    }
 }
 
 struct DwGeometry { int tiles_i, tiles_o, splits; int64_t rows_per_split; };
@@ -429,7 +442,7 @@ DwGeometry dw_geometry(int64_t n, int d_in, int d_out) {
     g.tiles_o = (d_out + kTile - 1) / kTile;
     const int64_t tiles = (int64_t)g.tiles_i * g.tiles_o;
     int64_t splits = 512 / tiles;                       // 2 workgroups per compute unit (the register budget) in total
-    const int64_t max_splits = (n + 2047) / 2048;       // at least 2048 rows per split
+    const int64_t max_splits = (n + 511) / 512;         // at least 512 rows per split
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
     g.rows_per_split = ((n + splits - 1) / splits + 31) / 32 * 32;
@@ -440,7 +453,7 @@ DwGeometry dw_geometry(int64_t n, int d_in, int d_out) {
 }
 
 gta_status check_dims(int d_in, int d_out, gta_dtype dtype) {
-    if (dtype != GTA_BF16) return fail(GTA_ERR_UNSUPPORTED, "the dense projections are implemented for bfloat16 only");
+    if (dtype != GTA_BF16 && dtype != GTA_F32) return fail(GTA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
     if (d_in <= 0 || d_out <= 0 || d_in % 16 != 0 || d_out % 8 != 0)
         return fail(GTA_ERR_UNSUPPORTED, "d_in must be a multiple of 16 and d_out a multiple of 8");
     if (d_in > 4096 || d_out > 4096) return fail(GTA_ERR_UNSUPPORTED, "dimensions up to 4096 are supported");
@@ -463,6 +476,9 @@ extern "C" GTA_API gta_status gta_linear(const void* X, const void* W, const voi
     if (((uintptr_t)X & 15) || ((uintptr_t)W & 15)) return fail(GTA_ERR_INVALID_ARG, "X and W must be 16-byte aligned");
     if (((uintptr_t)Y & 15) || ((uintptr_t)C & 15)) return fail(GTA_ERR_INVALID_ARG, "Y and C must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == GTA_F32)
+        return launch_linear_f32((const float*)X, (const float*)W, (const float*)C, (float*)Y, n, d_in, d_out,
+                                 trans_w, st);
     // Shape of a workgroup.  Every column tile of a row block re-reads the block's rows of X (out of
     // L2), so wider column tiles mean less traffic; the weight panel of the tile has to fit in LDS
     // next to the wavefronts' stages, with 8 wavefronts per compute unit in all (the register budget):
@@ -534,12 +550,17 @@ extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float
     {
         LaunchTimer t("linear_dw", n, 0, st);
         const int64_t blocks = (int64_t)(g.splits + 7) / 8 * 8 * g.tiles_i * g.tiles_o;
-        hipLaunchKernelGGL(k_linear_dw, dim3((unsigned)blocks), dim3(kThreads), 0, st, (const uint16_t*)X,
-                           (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split, g.tiles_i, g.tiles_o, g.splits);
+        if (dtype == GTA_F32)
+            launch_linear_dw_f32((const float*)X, (const float*)dY, partial, n, d_in, d_out, g.rows_per_split,
+                                 g.tiles_i, g.tiles_o, g.splits, st);
+        else
+            hipLaunchKernelGGL(k_linear_dw, dim3((unsigned)blocks), dim3(kThreads), 0, st, (const uint16_t*)X,
+                               (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split, g.tiles_i, g.tiles_o,
+                               g.splits);
     }
     {
         LaunchTimer t("linear_dw.reduce", 0, 0, st);
-        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, partial, dW,
+        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, st, partial, dW,
                            elems, g.splits);
     }
     GTA_HIP_TRY(hipGetLastError());

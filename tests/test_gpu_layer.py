@@ -36,3 +36,32 @@ def test_layer_forward_backward(name, shrink, heads, head_dim):
     assert_close("X'", to_f64(Xout), ref_out, tol)
     for label, got, want in zip(("dX", "dWq", "dWk", "dWv", "dWo"), (dX, dWq, dWk, dWv, dWo), ref):
         assert_close(label, to_f64(got), want, tol)
+
+
+@pytest.mark.parametrize("name,shrink,heads,head_dim", [("tiny", 1, 4, 16), ("mid", 4, 8, 16)])
+def test_layer_forward_backward_f32(name, shrink, heads, head_dim):
+    """The fp32 layer (the tiny and mid workloads are fp32).  Tolerance: each of the four stages a value
+    passes through (projection, attention, projection; their gradients likewise) stays within the fp32
+    bar of 1e-5 by itself; the errors of up to four stages add, so the composite is gated at 4e-5."""
+    import paper_2604_16715_amd as gta
+    w = gen.workload(name, shrink)
+    n, d = w.n_dst, heads * head_dim
+    print(f"layer f32 case {name}/{shrink} n={n} nnz={w.nnz} d={d}", flush=True)
+    mk = lambda shape, stream, scale: (gen.normal(shape, "f32", w.seed, stream) * np.float32(scale)).astype(np.float32)
+    X, dXout = mk((n, d), 2, 1.0), mk((n, d), 5, 1.0)
+    Ws = [mk((d, d), 10 + k, 0.125) for k in range(4)]
+    f64 = lambda a: a.astype(np.float64)
+    plan = gta.gta_plan_create(torch.from_numpy(w.indptr).cuda(), torch.from_numpy(w.indices).cuda(), n, keep_dz_min_nnz=1)
+    Xd, dXd = to_torch(X), to_torch(dXout)
+    Wd = [to_torch(a) for a in Ws]
+    Xout, saved = gta.gta_sga_layer_fwd(plan, Xd, *Wd, heads)
+    dX, dWq, dWk, dWv, dWo = gta.gta_sga_layer_bwd(plan, Xd, *Wd, saved, dXd, heads)
+    torch.cuda.synchronize()
+    ref_out, ref_saved = layer_ref.layer_forward(w.indptr, w.indices, f64(X), *[f64(a) for a in Ws], heads)
+    ref = layer_ref.layer_backward(w.indptr, w.indices, f64(X), *[f64(a) for a in Ws], heads, f64(dXout))
+    tol = 4e-5
+    assert_close("Q", to_f64(saved["Q"]).reshape(n, heads, head_dim), ref_saved["Q"], 1e-5)
+    assert_close("Y", to_f64(saved["Y"]).reshape(n, heads, head_dim), ref_saved["Y"], tol)
+    assert_close("X'", to_f64(Xout), ref_out, tol)
+    for label, got, want in zip(("dX", "dWq", "dWk", "dWv", "dWo"), (dX, dWq, dWk, dWv, dWo), ref):
+        assert_close(label, to_f64(got), want, tol)

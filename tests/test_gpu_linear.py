@@ -58,10 +58,10 @@ def test_linear_rejects_unsupported():
     W = torch.zeros((24, 16), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(gta.GtaError):
         gta.gta_linear(X, W)                     # d_in not a multiple of 16
-    X = torch.zeros((8, 32), dtype=torch.float32, device="cuda")
-    W = torch.zeros((32, 16), dtype=torch.float32, device="cuda")
+    X = torch.zeros((8, 512), dtype=torch.float32, device="cuda")
+    W = torch.zeros((512, 16), dtype=torch.float32, device="cuda")
     with pytest.raises(gta.GtaError):
-        gta.gta_linear(X, W)                     # fp32 not implemented for the projections
+        gta.gta_linear(X, W)                     # fp32 weight panel of 64 x 512 does not fit in LDS
 
 
 @pytest.mark.parametrize("n,d", [(257, 256), (1025, 256), (70001, 256), (129, 128), (66000 + 33, 128), (130, 64), (5, 48)])
@@ -81,3 +81,43 @@ def test_linear_accumulates_in_place(n, d):
             assert out.data_ptr() == acc.data_ptr()
             assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
 
+
+
+# ---- fp32 forms (v_mfma_f32_32x32x2_f32).  Tolerance: fp32 accumulation over d_in <= 496 terms per
+# output (and, for X^T dY, row splits of a few hundred rows summed in a second step) keeps the normwise
+# error near sqrt(terms) * 2^-24, i.e. ~1e-6; gated at the attention path's fp32 bar.
+F32_TOL = 1e-5
+
+
+def f32_matrix(rows, cols, seed, stream, scale=1.0):
+    return (gen.normal((rows, cols), "f32", seed, stream) * np.float32(scale)).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,d_in,d_out", [
+    (1000, 128, 128), (4097, 256, 256), (333, 64, 64), (2048, 64, 192), (129, 496, 72), (64, 16, 8), (1, 32, 40),
+    (5000, 48, 200), (169343, 128, 128), (140001, 64, 64),
+])
+def test_linear_forward_forms_f32(n, d_in, d_out):
+    import paper_2604_16715_amd as gta
+    print(f"linear f32 case n={n} d_in={d_in} d_out={d_out}", flush=True)
+    X, W, C = f32_matrix(n, d_in, 7, 2), f32_matrix(d_in, d_out, 7, 3, 0.125), f32_matrix(n, d_out, 7, 4)
+    Xf, Wf, Cf = (a.astype(np.float64) for a in (X, W, C))
+    Xd, Wd, Cd = to_torch(X), to_torch(W), to_torch(C)
+    assert_close("X W", to_f64(gta.gta_linear(Xd, Wd)), dense_ref.linear(Xf, Wf), F32_TOL)
+    assert_close("X W + C", to_f64(gta.gta_linear(Xd, Wd, Cd)), dense_ref.linear(Xf, Wf, Cf), F32_TOL)
+    Wt = to_torch(np.ascontiguousarray(W.T))
+    got_t = gta.gta_linear(Xd, Wt, Cd, trans_w=True)
+    assert_close("X W^T form", to_f64(got_t), dense_ref.linear(Xf, Wf, Cf), F32_TOL)
+    assert torch.equal(gta.gta_linear(Xd, Wd, Cd), got_t)     # same products in the same order
+    acc = Cd.clone()                                          # in place
+    assert torch.equal(gta.gta_linear(Xd, Wd, acc, Y=acc), got_t)
+
+
+@pytest.mark.parametrize("n,d_in,d_out", [(1000, 128, 128), (70000, 256, 256), (333, 64, 192), (31, 16, 8), (5000, 48, 200)])
+def test_linear_weight_gradient_f32(n, d_in, d_out):
+    import paper_2604_16715_amd as gta
+    print(f"linear_dw f32 case n={n} d_in={d_in} d_out={d_out}", flush=True)
+    X, dY = f32_matrix(n, d_in, 8, 2), f32_matrix(n, d_out, 8, 5)
+    got = gta.gta_linear_dw(to_torch(X), to_torch(dY))
+    assert_close("X^T dY", to_f64(got), dense_ref.linear_dw(X.astype(np.float64), dY.astype(np.float64)), F32_TOL)
+    assert torch.equal(got, gta.gta_linear_dw(to_torch(X), to_torch(dY)))   # fixed summation order
