@@ -18,6 +18,8 @@ struct Side {
     const int64_t* ptr = nullptr;   // device: row pointer of this side's pattern
     const int32_t* idx = nullptr;   // device: column ids (the other side's rows)
     int32_t* bin_rows = nullptr;    // device [n_rows]
+    int2* span = nullptr;           // device [n_rows]: (ptr[row], ptr[row + 1]) of bin_rows[r], so a kernel
+                                    // can fetch a row's id and its extent in one step instead of two
     int32_t* chunk_ptr = nullptr;   // device [n_chunked + 1]
     int4* chunks = nullptr;         // device [n_chunks] = (row, begin, end, chunks of row)
     int64_t bin_off[GTA_NUM_CLASSES + 1] = {0};   // host copy

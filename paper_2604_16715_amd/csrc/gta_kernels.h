@@ -118,6 +118,7 @@ struct RowSet {
     const int32_t* idx;    // its column ids
     const int32_t* eid;    // walk position -> index into per-entry arrays (null: identity)
     const int32_t* rows;   // plan order of the rows
+    const int2* span;      // (ptr[rows[r]], ptr[rows[r] + 1]) per plan position r
     int64_t begin, end;    // this launch covers rows[begin .. end)
 };
 struct ChunkSet {
@@ -183,10 +184,11 @@ __device__ __forceinline__ void body_packed(const typename Pass::Params& prm, co
     const int64_t r = rs.begin + wave * W + g;
     const bool active = r < rs.end;
     int row = 0, b = 0, e = 0;
-    if (active) {
+    if (active) {   // two independent loads
         row = rs.rows[r];
-        b = (int)rs.ptr[row];
-        e = (int)rs.ptr[row + 1];
+        const int2 sp = rs.span[r];
+        b = sp.x;
+        e = sp.y;
     }
     Pass ps;
     ps.init(prm, row, lig, active, true);
@@ -206,7 +208,8 @@ __device__ __forceinline__ void body_wave(const typename Pass::Params& prm, cons
     const int64_t r = rs.begin + block * kWavesPerBlock + (threadIdx.x >> 6);
     if (r >= rs.end) return;
     const int row = rs.rows[r];
-    const int b = (int)rs.ptr[row], e = (int)rs.ptr[row + 1];
+    const int2 sp = rs.span[r];
+    const int b = sp.x, e = sp.y;
     Pass ps;
     ps.init(prm, row, lig, true, g == 0);
     for (int bb = b; bb < e; bb += 64) {
@@ -321,8 +324,8 @@ gta_status launch_pass(const char* name, const typename Pass::Params& prm, const
     const Split sp = make_split(plan, side, Pass::G);
     char label[40];
     ChunkSet cs{sd.ptr, sd.idx, entry_map, sd.chunks, sd.chunk_ptr, sd.bin_rows, sd.n_chunks, sd.n_hub};
-    const RowSet wave{sd.ptr, sd.idx, entry_map, sd.bin_rows, sp.wave_begin, sp.wave_end};
-    const RowSet packed{sd.ptr, sd.idx, entry_map, sd.bin_rows, sp.pack_begin, sp.pack_end};
+    const RowSet wave{sd.ptr, sd.idx, entry_map, sd.bin_rows, sd.span, sp.wave_begin, sp.wave_end};
+    const RowSet packed{sd.ptr, sd.idx, entry_map, sd.bin_rows, sd.span, sp.pack_begin, sp.pack_end};
     const int64_t wave_blocks = (sp.wave_end - sp.wave_begin + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t per_block = kWavesPerBlock * W;
     const int64_t pack_blocks = (sp.pack_end - sp.pack_begin + per_block - 1) / per_block;

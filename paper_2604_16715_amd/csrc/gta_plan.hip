@@ -218,6 +218,14 @@ __global__ void k_row_of_entry(const int32_t* row_of_pos, const int32_t* t_eid, 
     if (p < nnz) t_indices[p] = row_of_pos[t_eid[p]];
 }
 
+// extent of every row in plan order (positions fit in 32 bits)
+__global__ void k_row_spans(const int64_t* ptr, const int32_t* bin_rows, int64_t n_rows, int2* span) {
+    int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    const int row = bin_rows[r];
+    span[r] = make_int2((int)ptr[row], (int)ptr[row + 1]);
+}
+
 // ------------------------------------------------------------------ chunk tables
 __global__ void k_chunk_count(const int64_t* ptr, const int32_t* bin_rows, int64_t n_chunked,
                               int hub_chunk, int32_t* cnt) {
@@ -267,7 +275,7 @@ bool resolve_opts(const gta_plan_opts* o, Opts* r) {
 }
 
 struct Layout {
-    size_t bin_rows[2], chunk_ptr[2], chunks[2], t_indptr, t_indices, t_eid, t_pos;
+    size_t bin_rows[2], span[2], chunk_ptr[2], chunks[2], t_indptr, t_indices, t_eid, t_pos;
     size_t key_a, key_b, val_a, val_b, hist, tile_sum, stats, flag, total;
     int64_t max_chunked[2], max_chunks[2], sort_cap, hist_cap, tile_cap;
 };
@@ -280,6 +288,7 @@ void make_layout(int64_t n_dst, int64_t n_src, int64_t nnz, const Opts& o, Layou
         L->max_chunked[s] = std::min<int64_t>(n_rows[s], nnz / ((int64_t)o.wave + 1));
         L->max_chunks[s] = nnz / o.chunk + L->max_chunked[s];
         L->bin_rows[s] = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, n_rows[s]));
+        L->span[s] = take(sizeof(int2) * (size_t)std::max<int64_t>(1, n_rows[s]));
         L->chunk_ptr[s] = take(sizeof(int32_t) * (size_t)(L->max_chunked[s] + 1));
         L->chunks[s] = take(sizeof(int4) * (size_t)std::max<int64_t>(1, L->max_chunks[s]));
     }
@@ -352,6 +361,7 @@ struct Builder {
         sd->ptr = ptr;
         sd->idx = idx;
         sd->bin_rows = at<int32_t>(L.bin_rows[s]);
+        sd->span = at<int2>(L.span[s]);
         sd->chunk_ptr = at<int32_t>(L.chunk_ptr[s]);
         sd->chunks = at<int4>(L.chunks[s]);
         unsigned long long* stats = at<unsigned long long>(L.stats);
@@ -364,9 +374,11 @@ struct Builder {
         int32_t* vs;
         gta_status rc = radix_sort(n_rows, 8, &ks, &vs);
         if (rc != GTA_OK) return rc;
-        if (n_rows > 0)
+        if (n_rows > 0) {
             GTA_HIP_TRY(hipMemcpyAsync(sd->bin_rows, vs, sizeof(int32_t) * (size_t)n_rows,
                                        hipMemcpyDeviceToDevice, st));
+            hipLaunchKernelGGL(k_row_spans, grid_for(n_rows, 256), dim3(256), 0, st, ptr, sd->bin_rows, n_rows, sd->span);
+        }
         unsigned long long h_stats[2 * GTA_NUM_CLASSES];
         GTA_HIP_TRY(hipMemcpyAsync(h_stats, stats, sizeof(h_stats), hipMemcpyDeviceToHost, st));
         GTA_HIP_TRY(hipStreamSynchronize(st));
