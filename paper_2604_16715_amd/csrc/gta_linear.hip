@@ -310,20 +310,32 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
 }
 
 // ---------------------------------------------------------------------------------------------
-// dW[d_in, d_out] = X^T dY, summed over the n rows.  Workgroup: a 128 x 128 tile of dW over one
-// block of rows; wavefront (w / 2, w % 2) owns a 64 x 64 quarter.  Both operands have the
-// reduction index (the row) as their slow index, so each 32-row block is transposed into LDS:
-// a thread loads 4 consecutive rows of the same 8 columns and writes one 8-byte word per column.
-// LDS rows are 18 dwords apart and consecutive lanes write consecutive row quads, which spreads
-// both the 8-byte writes and the 8-byte fragment reads over all banks.
+// dW[d_in, d_out] = X^T dY, summed over the n rows.  A workgroup of WI x WO wavefronts owns a
+// TI x TO tile of dW (TI = 32 WI AI, TO = 32 WO AO) over one block of rows; wavefront (wi, wo) owns
+// AI x AO accumulator tiles of 32 x 32.  Two shapes are used: 128 x 128 with 4 wavefronts, and
+// 256 x 256 with 8 wavefronts when a dimension exceeds 128 — there a workgroup covers the whole
+// gradient at d = 256, so X and dY are each read exactly once.  Both operands have the reduction
+// index (the row) as their slow index, so each 32-row block is transposed into LDS: a thread loads
+// 4 consecutive rows of the same 8 columns and writes one 8-byte word per column.  LDS rows are 18
+// dwords apart and consecutive lanes write consecutive row quads, which spreads both the 8-byte
+// writes and the 8-byte fragment reads over all banks.  The LDS block is double-buffered (one
+// workgroup barrier per 32 rows) and the global loads run Q blocks ahead in registers.
 // Row blocks are reduced afterwards in a fixed order (k_reduce_partials): no atomics.
-constexpr int kDwQueue = 4;
+constexpr int kDwKB = 32, kDwPitch = kDwKB + 4;   // rows per block; 36 bf16 = 18 dwords per LDS row
 
-__global__ void __launch_bounds__(kThreads, 2)
+template <int WI, int WO, int AI, int AO>
+constexpr size_t dw_lds_bytes() { return sizeof(uint16_t) * 2 * (size_t)(32 * WI * AI + 32 * WO * AO) * kDwPitch; }
+
+template <int WI, int WO, int AI, int AO, int Q>
+__global__ void __launch_bounds__(64 * WI * WO, 8 / (WI * WO))   // 8 wavefronts per compute unit
 k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, float* __restrict__ partial,
             int64_t n, int d_in, int d_out, int64_t rows_per_split, int tiles_i, int tiles_o, int splits) {
-    constexpr int KB = 32, pitch = KB + 4;   // 36 bf16 = 18 dwords
-    __shared__ __align__(16) uint16_t xs[kTile * pitch], ys[kTile * pitch];
+    constexpr int T = 64 * WI * WO, TI = 32 * WI * AI, TO = 32 * WO * AO, KB = kDwKB, pitch = kDwPitch;
+    static_assert(TI == T / 2 && TO == T / 2, "half of the threads stage X, the other half dY, one unit each");
+    static_assert(Q % 2 == 0, "the buffer a queue slot goes to must not depend on the outer iteration");
+    extern __shared__ __align__(16) unsigned char dw_lds[];
+    uint16_t* xs = reinterpret_cast<uint16_t*>(dw_lds);   // [2][TI][pitch]
+    uint16_t* ys = xs + 2 * TI * pitch;                   // [2][TO][pitch]
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 5, r32 = lane & 31;
     // the tiles of one row split get ids 8 apart (same XCD) so that the rows they share hit in one L2
     const int64_t bid = blockIdx.x, jj = bid >> 3;
@@ -331,30 +343,31 @@ k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, flo
     const int tile = (int)(jj % tiles);
     const int64_t split = (jj / tiles) * 8 + (bid & 7);
     if (split >= splits) return;   // whole workgroup leaves together
-    const int i0 = (tile % tiles_i) * kTile, o0 = (tile / tiles_i) * kTile;
+    const int i0 = (tile % tiles_i) * TI, o0 = (tile / tiles_i) * TO;
     const int64_t rbeg = split * rows_per_split;
     const int64_t rend = rbeg + rows_per_split < n ? rbeg + rows_per_split : n;
-    const int wi = w >> 1, wo = w & 1;
+    const int wi = w / WO, wo = w % WO;
 
-    // loader role: threads 0..127 stage X, 128..255 stage dY; unit = 8 columns x 4 rows
-    const bool loads_x = threadIdx.x < 128;
-    const int lt = threadIdx.x & 127, rq = lt & 7, cu = lt >> 3;
+    // loader role: the first T/2 threads stage X, the others dY; unit = 8 columns x 4 rows
+    const bool loads_x = threadIdx.x < T / 2;
+    const int lt = threadIdx.x % (T / 2), rq = lt & 7, cu = lt >> 3;
     const uint16_t* src = loads_x ? X : dY;
     const int ld = loads_x ? d_in : d_out;
     const int cbase = (loads_x ? i0 : o0) + cu * 8;
     const bool col_ok = cbase < ld;
     uint16_t* dst = (loads_x ? xs : ys) + (cu * 8) * pitch + rq * 4;
+    constexpr int buf_stride = T / 2 * pitch;   // elements between the two buffers of an operand
 
-    floatx16 acc[2][2];
+    floatx16 acc[AI][AO];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < AI; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < AO; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // register queue: the loads of row block s + kDwQueue are issued when block s is written to LDS
-    uint4 queue[kDwQueue][4];
+    // register queue: the loads of row block s + Q are issued when block s is written to LDS
+    uint4 queue[Q][4];
     auto fetch = [&](uint4 (&slot)[4], int64_t r0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -364,50 +377,58 @@ k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, flo
         }
     };
 #pragma unroll
-    for (int i = 0; i < kDwQueue; ++i) fetch(queue[i], rbeg + (int64_t)i * KB);
-    for (int64_t rb = rbeg; rb < rend; rb += (int64_t)kDwQueue * KB) {
+    for (int i = 0; i < Q; ++i) fetch(queue[i], rbeg + (int64_t)i * KB);
+    for (int64_t rb = rbeg; rb < rend; rb += (int64_t)Q * KB) {
 #pragma unroll
-        for (int i = 0; i < kDwQueue; ++i) {
+        for (int i = 0; i < Q; ++i) {
             const int64_t r0 = rb + (int64_t)i * KB;
             if (r0 >= rend) break;   // uniform over the workgroup
-            __syncthreads();   // previous block's fragments have been read
+            // Buffer i & 1 was last read two blocks ago; every wavefront has passed the barrier of the
+            // block in between, which it reaches only after those reads.
+            uint16_t* my_dst = dst + (i & 1) * buf_stride;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {   // column e of the unit: its four rows become one 8-byte word
                 const uint32_t lo = half_of(queue[i][0], e) | (half_of(queue[i][1], e) << 16);
                 const uint32_t hi = half_of(queue[i][2], e) | (half_of(queue[i][3], e) << 16);
-                *reinterpret_cast<uint2*>(dst + e * pitch) = make_uint2(lo, hi);
+                *reinterpret_cast<uint2*>(my_dst + e * pitch) = make_uint2(lo, hi);
             }
             __syncthreads();
-            fetch(queue[i], r0 + (int64_t)kDwQueue * KB);
+            fetch(queue[i], r0 + (int64_t)Q * KB);
+            const uint16_t* xb = xs + (i & 1) * buf_stride + (32 * AI * wi + r32) * pitch + 8 * g;
+            const uint16_t* yb = ys + (i & 1) * buf_stride + (32 * AO * wo + r32) * pitch + 8 * g;
 #pragma unroll
             for (int ks = 0; ks < KB; ks += 16) {
-                uint4 af[2], bf[2];
+                uint4 af[AI], bf[AO];
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {   // rows are 8-byte aligned only: two 8-byte reads per fragment
-                    const uint2* pa = reinterpret_cast<const uint2*>(xs + (64 * wi + 32 * t + r32) * pitch + ks + 8 * g);
-                    const uint2* pb = reinterpret_cast<const uint2*>(ys + (64 * wo + 32 * t + r32) * pitch + ks + 8 * g);
-                    const uint2 a0 = pa[0], a1 = pa[1], b0 = pb[0], b1 = pb[1];
+                for (int t = 0; t < AI; ++t) {   // rows are 8-byte aligned only: two 8-byte reads per fragment
+                    const uint2* pa = reinterpret_cast<const uint2*>(xb + 32 * t * pitch + ks);
+                    const uint2 a0 = pa[0], a1 = pa[1];
                     af[t] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                }
+#pragma unroll
+                for (int t = 0; t < AO; ++t) {
+                    const uint2* pb = reinterpret_cast<const uint2*>(yb + 32 * t * pitch + ks);
+                    const uint2 b0 = pb[0], b1 = pb[1];
                     bf[t] = make_uint4(b0.x, b0.y, b1.x, b1.y);
                 }
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < AI; ++a)
 #pragma unroll
-                    for (int b = 0; b < 2; ++b)
+                    for (int b = 0; b < AO; ++b)
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(af[a]), as_frag(bf[b]), acc[a][b], 0, 0, 0);
             }
         }
     }
     float* out = partial + split * d_in * d_out;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < AI; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int o = o0 + 64 * wo + 32 * b + r32;
+        for (int b = 0; b < AO; ++b) {
+            const int o = o0 + 32 * AO * wo + 32 * b + r32;
             if (o >= d_out) continue;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int i = i0 + 64 * wi + 32 * a + out_row(v, lane);
+                const int i = i0 + 32 * AI * wi + 32 * a + out_row(v, lane);
                 if (i < d_in) out[(int64_t)i * d_out + o] = acc[a][b][v];
             }
         }
@@ -434,14 +455,16 @@ k_reduce_partials(const float* __restrict__ partial, float* __restrict__ dW, int
     }
 }
 
-struct DwGeometry { int tiles_i, tiles_o, splits; int64_t rows_per_split; };
+struct DwGeometry { int tile, tiles_i, tiles_o, splits; int64_t rows_per_split; };
 
-DwGeometry dw_geometry(int64_t n, int d_in, int d_out) {
+// tile: 256 when a dimension exceeds 128 (bf16 only: the 256 x 256 shape), else 128
+DwGeometry dw_geometry(int64_t n, int d_in, int d_out, gta_dtype dtype) {
     DwGeometry g;
-    g.tiles_i = (d_in + kTile - 1) / kTile;
-    g.tiles_o = (d_out + kTile - 1) / kTile;
+    g.tile = dtype == GTA_BF16 && (d_in > kTile || d_out > kTile) ? 256 : kTile;
+    g.tiles_i = (d_in + g.tile - 1) / g.tile;
+    g.tiles_o = (d_out + g.tile - 1) / g.tile;
     const int64_t tiles = (int64_t)g.tiles_i * g.tiles_o;
-    int64_t splits = 512 / tiles;                       // 2 workgroups per compute unit (the register budget) in total
+    int64_t splits = (g.tile == 256 ? 256 : 512) / tiles;   // 8 wavefronts per compute unit (the register budget) in total
     const int64_t max_splits = (n + 511) / 512;         // at least 512 rows per split
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
@@ -528,8 +551,8 @@ extern "C" GTA_API gta_status gta_linear(const void* X, const void* W, const voi
 
 extern "C" GTA_API size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d_out) {
     if (n < 0 || d_in <= 0 || d_out <= 0) return 0;
-    const DwGeometry g = dw_geometry(n, d_in, d_out);
-    return sizeof(float) * (size_t)g.splits * (size_t)d_in * (size_t)d_out + 256;
+    const int splits = std::max(dw_geometry(n, d_in, d_out, GTA_BF16).splits, dw_geometry(n, d_in, d_out, GTA_F32).splits);
+    return sizeof(float) * (size_t)splits * (size_t)d_in * (size_t)d_out + 256;   // enough for either element type
 }
 
 extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in,
@@ -544,7 +567,7 @@ extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float
     const size_t need = gta_linear_dw_scratch_bytes(n, d_in, d_out);
     if (!scratch || scratch_bytes < need) return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const DwGeometry g = dw_geometry(n, d_in, d_out);
+    const DwGeometry g = dw_geometry(n, d_in, d_out, dtype);
     const int64_t elems = (int64_t)d_in * d_out;
     float* partial = static_cast<float*>(scratch);
     {
@@ -553,10 +576,19 @@ extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float
         if (dtype == GTA_F32)
             launch_linear_dw_f32((const float*)X, (const float*)dY, partial, n, d_in, d_out, g.rows_per_split,
                                  g.tiles_i, g.tiles_o, g.splits, st);
-        else
-            hipLaunchKernelGGL(k_linear_dw, dim3((unsigned)blocks), dim3(kThreads), 0, st, (const uint16_t*)X,
-                               (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split, g.tiles_i, g.tiles_o,
-                               g.splits);
+        else if (g.tile == 256) {   // 8 wavefronts, each 128 x 64 of the 256 x 256 tile
+            constexpr size_t lds = dw_lds_bytes<2, 4, 4, 2>();
+            GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear_dw<2, 4, 4, 2, 2>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            hipLaunchKernelGGL((k_linear_dw<2, 4, 4, 2, 2>), dim3((unsigned)blocks), dim3(512), lds, st,
+                               (const uint16_t*)X, (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split,
+                               g.tiles_i, g.tiles_o, g.splits);
+        } else {                    // 4 wavefronts, each 64 x 64 of the 128 x 128 tile
+            constexpr size_t lds = dw_lds_bytes<2, 2, 2, 2>();
+            hipLaunchKernelGGL((k_linear_dw<2, 2, 2, 2, 4>), dim3((unsigned)blocks), dim3(256), lds, st,
+                               (const uint16_t*)X, (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split,
+                               g.tiles_i, g.tiles_o, g.splits);
+        }
     }
     {
         LaunchTimer t("linear_dw.reduce", 0, 0, st);
