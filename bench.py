@@ -319,7 +319,10 @@ def main() -> int:
                    "heads": w.heads, "head_dim": w.head_dim, "accumulate": "f32",
                    "backward": "recompute-per-entry" if args.lean_scratch else "dZ-kept-per-entry",
                    "plan_ms": plan_ms, "wave_max_deg": int(plan.info().wave_max_deg),
-                   "hub_chunk": int(plan.info().hub_chunk)},
+                   "hub_chunk": int(plan.info().hub_chunk),
+                   "plan_workspace_bytes": int(plan.workspace.numel()),
+                   "scratch_bytes": int(plan.scratch(w.heads, w.head_dim, 1 if w.dtype == "bf16" else 0,
+                                                     args.lean_scratch).numel())},
         "hbm": {"algorithmic_bytes_per_step": total_bytes,
                 "achieved_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
                 "frac_of_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
