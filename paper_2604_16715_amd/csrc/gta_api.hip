@@ -161,6 +161,10 @@ gta_status check_common(const gta_plan* plan, const int64_t* indptr, const int32
     if (n_dst != plan->n_dst || n_src != plan->n_src)
         return fail(GTA_ERR_INVALID_ARG, "n_dst/n_src differ from the plan's (%lld, %lld)",
                     (long long)plan->n_dst, (long long)plan->n_src);
+    int device = -1;
+    GTA_HIP_TRY(hipGetDevice(&device));
+    if (device != plan->device)
+        return fail(GTA_ERR_INVALID_ARG, "the plan lives on device %d, the current device is %d", plan->device, device);
     gta_status rc = make_shape(heads, head_dim, dtype, sh);
     if (rc != GTA_OK) return rc;
     if (!(*scale > 0.f)) *scale = 1.0f / sqrtf((float)head_dim);

@@ -238,6 +238,10 @@ gta_status check_graph(const gta_plan* plan, const int64_t* indptr, const int32_
         return fail(GTA_ERR_INVALID_ARG, "indptr/indices differ from the arrays the plan was built for");
     if (n_dst != plan->n_dst || (n_src >= 0 && n_src != plan->n_src))
         return fail(GTA_ERR_INVALID_ARG, "n_dst/n_src differ from the plan's");
+    int device = -1;
+    GTA_HIP_TRY(hipGetDevice(&device));
+    if (device != plan->device)
+        return fail(GTA_ERR_INVALID_ARG, "the plan lives on device %d, the current device is %d", plan->device, device);
     return GTA_OK;
 }
 
