@@ -58,8 +58,8 @@ typedef enum { GTA_F32 = 0, GTA_BF16 = 1 } gta_dtype;
 
 typedef struct gta_plan gta_plan; /* opaque, host-side handle */
 
-/* Scheduling thresholds; 0 selects the default.  wave_max_deg and hub_chunk must be powers of
- * two with hub_chunk >= wave_max_deg.
+/* Scheduling thresholds; 0 selects the default (wave_max_deg 128, hub_chunk 2048).  wave_max_deg and
+ * hub_chunk must be powers of two with hub_chunk >= wave_max_deg.
  *   rows with degree <= wave_max_deg  : one wavefront (or a fraction of one) per row
  *   rows with degree  > wave_max_deg  : cut into chunks of hub_chunk entries, one workgroup per
  *                                       chunk; rows with more than one chunk are merged afterwards

@@ -76,7 +76,7 @@ def transpose_ref(indptr: np.ndarray, indices: np.ndarray, n_src: int) -> dict:
                 t_eid=order.astype(np.int32))
 
 
-def plan_ref(indptr, indices, n_src, wave_max_deg=512, hub_chunk=2048) -> dict:
+def plan_ref(indptr, indices, n_src, wave_max_deg=128, hub_chunk=2048) -> dict:
     out = {"dst": bin_rows_ref(indptr, wave_max_deg, hub_chunk)}
     tr = transpose_ref(indptr, indices, n_src)
     out.update(tr)

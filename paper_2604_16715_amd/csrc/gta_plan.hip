@@ -264,7 +264,7 @@ struct Opts { int pack, wave, chunk, validate; int64_t keep_dz; };
 
 bool resolve_opts(const gta_plan_opts* o, Opts* r) {
     r->pack = o && o->pack_max_deg > 0 ? o->pack_max_deg : 0;
-    r->wave = o && o->wave_max_deg > 0 ? o->wave_max_deg : 512;
+    r->wave = o && o->wave_max_deg > 0 ? o->wave_max_deg : 128;
     r->chunk = o && o->hub_chunk > 0 ? o->hub_chunk : 2048;
     r->validate = o ? o->validate : 0;
     r->keep_dz = !o || o->keep_dz_min_nnz == 0 ? 262144 : (o->keep_dz_min_nnz < 0 ? INT64_MAX : o->keep_dz_min_nnz);

@@ -31,8 +31,8 @@ def build_and_compare(indptr, indices, n_src, wave_max_deg, hub_chunk):
 
 
 @pytest.mark.parametrize("name,shrink,wmax,chunk", [
-    ("tiny", 1, 512, 2048), ("tiny", 1, 8, 32), ("mid", 1, 512, 2048), ("mid", 4, 16, 16),
-    ("large", 32, 512, 2048), ("partition", 32, 64, 256), ("skew", 64, 512, 2048),
+    ("tiny", 1, 128, 2048), ("tiny", 1, 8, 32), ("mid", 1, 128, 2048), ("mid", 4, 16, 16),
+    ("large", 32, 128, 2048), ("partition", 32, 64, 256), ("skew", 64, 512, 2048),
 ])
 def test_plan_matches_reference(name, shrink, wmax, chunk):
     print(f"plan case {name} shrink={shrink} wave_max={wmax} hub_chunk={chunk}", flush=True)
