@@ -192,6 +192,143 @@ k_edge_softmax_bwd(const int64_t* ptr, const int32_t* rows, int64_t row_begin, i
     }
 }
 
+// The same two kernels with 16 bytes per lane, for H >= 4 (then a row's values start 16-byte
+// aligned and a lane's four consecutive values are four consecutive heads: (4 t + c) % H for
+// component c, the same for every step since H divides 4 TEAM).  With 4-byte accesses these kernels
+// are bound by the number of memory instructions, not by bytes.  Lanes that share heads are H / 4
+// apart, so the team reductions run once per component with that stride.
+constexpr int kSoftmaxHeld4 = 4;   // float4 per lane held in registers: rows of up to 16 TEAM values are read once
+
+template <int TEAM>
+__global__ void __launch_bounds__(kBlockThreads)
+k_edge_softmax4(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64_t row_end, int H,
+                float scale2, const float* Z, float* U, float* lse) {
+    __shared__ float lds[kBlockThreads * 2];
+    constexpr int kTeams = kBlockThreads / TEAM;
+    const int t = threadIdx.x % TEAM, HQ = H / 4;
+    for (int64_t base = row_begin + (int64_t)blockIdx.x * kTeams; base < row_end; base += (int64_t)gridDim.x * kTeams) {
+        const int64_t r = base + threadIdx.x / TEAM;
+        const bool active = r < row_end;   // uniform over the team (and over the block when TEAM == block)
+        int64_t b = 0, e = 0;
+        int row = 0;
+        if (active) {
+            row = rows[r];
+            b = ptr[row] * H;
+            e = ptr[row + 1] * H;
+        }
+        float4 held[kSoftmaxHeld4];
+        float m[4] = {kNegBig, kNegBig, kNegBig, kNegBig}, l[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < kSoftmaxHeld4; ++k) {
+            const int64_t x = b + 4 * (t + (int64_t)k * TEAM);
+            held[k] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (x < e) {
+                const float4 z = *reinterpret_cast<const float4*>(Z + x);
+                held[k] = make_float4(z.x * scale2, z.y * scale2, z.z * scale2, z.w * scale2);
+            }
+            m[0] = fmaxf(m[0], held[k].x); m[1] = fmaxf(m[1], held[k].y);
+            m[2] = fmaxf(m[2], held[k].z); m[3] = fmaxf(m[3], held[k].w);
+        }
+#pragma unroll
+        for (int k = 0; k < kSoftmaxHeld4; ++k) {   // exp2(-inf) = 0 for the slots past the end
+            l[0] += fast_exp2(held[k].x - m[0]); l[1] += fast_exp2(held[k].y - m[1]);
+            l[2] += fast_exp2(held[k].z - m[2]); l[3] += fast_exp2(held[k].w - m[3]);
+        }
+        for (int64_t x = b + 4 * (t + (int64_t)kSoftmaxHeld4 * TEAM); x < e; x += 4 * TEAM) {
+            const float4 z = *reinterpret_cast<const float4*>(Z + x);
+            const float s[4] = {z.x * scale2, z.y * scale2, z.z * scale2, z.w * scale2};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float mn = fmaxf(m[c], s[c]);
+                l[c] = l[c] * fast_exp2(m[c] - mn) + fast_exp2(s[c] - mn);
+                m[c] = mn;
+            }
+        }
+        float lse2[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            TeamReduce<TEAM>::softmax(m[c], l[c], HQ, lds);
+            lse2[c] = m[c] + fast_log2(l[c]);
+        }
+#pragma unroll
+        for (int k = 0; k < kSoftmaxHeld4; ++k) {
+            const int64_t x = b + 4 * (t + (int64_t)k * TEAM);
+            if (x < e)
+                *reinterpret_cast<float4*>(U + x) =
+                    make_float4(fast_exp2(held[k].x - lse2[0]), fast_exp2(held[k].y - lse2[1]),
+                                fast_exp2(held[k].z - lse2[2]), fast_exp2(held[k].w - lse2[3]));
+        }
+        for (int64_t x = b + 4 * (t + (int64_t)kSoftmaxHeld4 * TEAM); x < e; x += 4 * TEAM) {
+            const float4 z = *reinterpret_cast<const float4*>(Z + x);
+            *reinterpret_cast<float4*>(U + x) =
+                make_float4(fast_exp2(z.x * scale2 - lse2[0]), fast_exp2(z.y * scale2 - lse2[1]),
+                            fast_exp2(z.z * scale2 - lse2[2]), fast_exp2(z.w * scale2 - lse2[3]));
+        }
+        if (active && lse && t < HQ) {
+            const bool any = e > b;
+            *reinterpret_cast<float4*>(lse + (int64_t)row * H + 4 * t) =
+                any ? make_float4(lse2[0] * kLn2, lse2[1] * kLn2, lse2[2] * kLn2, lse2[3] * kLn2)
+                    : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+    }
+}
+
+template <int TEAM>
+__global__ void __launch_bounds__(kBlockThreads)
+k_edge_softmax_bwd4(const int64_t* ptr, const int32_t* rows, int64_t row_begin, int64_t row_end, int H,
+                    float scale, const float* U, const float* dU, float* dZ) {
+    __shared__ float lds[kBlockThreads * 2];
+    constexpr int kTeams = kBlockThreads / TEAM;
+    const int t = threadIdx.x % TEAM, HQ = H / 4;
+    for (int64_t base = row_begin + (int64_t)blockIdx.x * kTeams; base < row_end; base += (int64_t)gridDim.x * kTeams) {
+        const int64_t r = base + threadIdx.x / TEAM;
+        int64_t b = 0, e = 0;
+        if (r < row_end) {
+            const int row = rows[r];
+            b = ptr[row] * H;
+            e = ptr[row + 1] * H;
+        }
+        float4 hu[kSoftmaxHeld4], hd[kSoftmaxHeld4];
+        float dot[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < kSoftmaxHeld4; ++k) {
+            const int64_t x = b + 4 * (t + (int64_t)k * TEAM);
+            hu[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            hd[k] = hu[k];
+            if (x < e) {
+                hu[k] = *reinterpret_cast<const float4*>(U + x);
+                hd[k] = *reinterpret_cast<const float4*>(dU + x);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kSoftmaxHeld4; ++k) {
+            dot[0] = fmaf(hu[k].x, hd[k].x, dot[0]); dot[1] = fmaf(hu[k].y, hd[k].y, dot[1]);
+            dot[2] = fmaf(hu[k].z, hd[k].z, dot[2]); dot[3] = fmaf(hu[k].w, hd[k].w, dot[3]);
+        }
+        for (int64_t x = b + 4 * (t + (int64_t)kSoftmaxHeld4 * TEAM); x < e; x += 4 * TEAM) {
+            const float4 u = *reinterpret_cast<const float4*>(U + x), d = *reinterpret_cast<const float4*>(dU + x);
+            dot[0] = fmaf(u.x, d.x, dot[0]); dot[1] = fmaf(u.y, d.y, dot[1]);
+            dot[2] = fmaf(u.z, d.z, dot[2]); dot[3] = fmaf(u.w, d.w, dot[3]);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dot[c] = TeamReduce<TEAM>::sum(dot[c], HQ, lds);
+#pragma unroll
+        for (int k = 0; k < kSoftmaxHeld4; ++k) {
+            const int64_t x = b + 4 * (t + (int64_t)k * TEAM);
+            if (x < e)
+                *reinterpret_cast<float4*>(dZ + x) =
+                    make_float4(scale * hu[k].x * (hd[k].x - dot[0]), scale * hu[k].y * (hd[k].y - dot[1]),
+                                scale * hu[k].z * (hd[k].z - dot[2]), scale * hu[k].w * (hd[k].w - dot[3]));
+        }
+        for (int64_t x = b + 4 * (t + (int64_t)kSoftmaxHeld4 * TEAM); x < e; x += 4 * TEAM) {
+            const float4 u = *reinterpret_cast<const float4*>(U + x), d = *reinterpret_cast<const float4*>(dU + x);
+            *reinterpret_cast<float4*>(dZ + x) =
+                make_float4(scale * u.x * (d.x - dot[0]), scale * u.y * (d.y - dot[1]),
+                            scale * u.z * (d.z - dot[2]), scale * u.w * (d.w - dot[3]));
+        }
+    }
+}
+
 template <class T> gta_status run_sddmm(const gta_plan* plan, const Shape& sh, const void* X, const void* Y,
                                         float* Z, float* partial, hipStream_t st) {
 #define GTA_CALL(LHc, Gc)                                                                        \
@@ -331,10 +468,17 @@ extern "C" GTA_API gta_status gta_edge_softmax(const gta_plan* plan, const int64
     if (plan->nnz > 0 && (!Z || !U)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Side& sd = plan->side[0];
+    // 16 bytes per lane when a row's values are 16-byte aligned and a lane's four values are four heads
+    const bool vec4 = heads >= 4 && (((uintptr_t)Z | (uintptr_t)U | (uintptr_t)lse) & 15) == 0;
     LaunchTimer t("edge_softmax", sd.n_rows, plan->nnz, st);
     return softmax_launches(plan, heads, "edge_softmax", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
-        hipLaunchKernelGGL(k_edge_softmax<decltype(team)::value>, dim3((unsigned)std::min<int64_t>(blocks, kSoftmaxMaxBlocks)), dim3(kBlockThreads), 0, st,
-                           sd.ptr, sd.bin_rows, rb, re, heads, scale * kLog2e, Z, U, lse);
+        const dim3 grid((unsigned)std::min<int64_t>(blocks, kSoftmaxMaxBlocks));
+        if (vec4)
+            hipLaunchKernelGGL(k_edge_softmax4<decltype(team)::value>, grid, dim3(kBlockThreads), 0, st, sd.ptr,
+                               sd.bin_rows, rb, re, heads, scale * kLog2e, Z, U, lse);
+        else
+            hipLaunchKernelGGL(k_edge_softmax<decltype(team)::value>, grid, dim3(kBlockThreads), 0, st, sd.ptr,
+                               sd.bin_rows, rb, re, heads, scale * kLog2e, Z, U, lse);
     });
 }
 
@@ -348,9 +492,15 @@ extern "C" GTA_API gta_status gta_edge_softmax_bwd(const gta_plan* plan, const i
     if (plan->nnz > 0 && (!U || !dU || !dZ)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Side& sd = plan->side[0];
+    const bool vec4 = heads >= 4 && (((uintptr_t)U | (uintptr_t)dU | (uintptr_t)dZ) & 15) == 0;
     LaunchTimer t("edge_softmax_bwd", sd.n_rows, plan->nnz, st);
     return softmax_launches(plan, heads, "edge_softmax_bwd", [&](auto team, int64_t rb, int64_t re, int64_t blocks) {
-        hipLaunchKernelGGL(k_edge_softmax_bwd<decltype(team)::value>, dim3((unsigned)std::min<int64_t>(blocks, kSoftmaxMaxBlocks)), dim3(kBlockThreads), 0, st,
-                           sd.ptr, sd.bin_rows, rb, re, heads, scale, U, dU, dZ);
+        const dim3 grid((unsigned)std::min<int64_t>(blocks, kSoftmaxMaxBlocks));
+        if (vec4)
+            hipLaunchKernelGGL(k_edge_softmax_bwd4<decltype(team)::value>, grid, dim3(kBlockThreads), 0, st, sd.ptr,
+                               sd.bin_rows, rb, re, heads, scale, U, dU, dZ);
+        else
+            hipLaunchKernelGGL(k_edge_softmax_bwd<decltype(team)::value>, grid, dim3(kBlockThreads), 0, st, sd.ptr,
+                               sd.bin_rows, rb, re, heads, scale, U, dU, dZ);
     });
 }

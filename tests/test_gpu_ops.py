@@ -82,3 +82,38 @@ def test_operators_edge_cases():
     Z = torch.zeros((int(indptr[-1]), 4), device="cuda")
     with pytest.raises(gta.GtaError):
         gta.gta_edge_softmax(plan, Z, 0.0)          # scale must be given
+
+
+@pytest.mark.parametrize("heads", [1, 2, 4, 8, 16, 32, 64])
+@pytest.mark.parametrize("kw", [None, dict(wave_max_deg=8, hub_chunk=32)])
+def test_edge_softmax_all_head_counts(heads, kw):
+    """Both access widths (4 bytes per lane for H < 4, 16 bytes for H >= 4, also on an unaligned
+    view) and all three team sizes, against the oracle's operators."""
+    import oracle
+    import paper_2604_16715_amd as gta
+    print(f"edge softmax heads={heads} plan={kw}", flush=True)
+    indptr, indices = gen.random_csr(400, 500, 9000, seed=40 + heads, allow_dup=True, sort_rows=False)
+    indptr = indptr.copy()
+    E = int(indptr[-1])
+    rng = np.random.Generator(np.random.Philox(heads))
+    Z = (3.0 * rng.standard_normal((E, heads))).astype(np.float32)
+    dU = rng.standard_normal((E, heads)).astype(np.float32)
+    scale = 0.7
+    plan = gta.gta_plan_create(torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), 500, **(kw or {}))
+    ref_U, ref_lse = oracle.edge_softmax(indptr, Z.astype(np.float64), scale)
+    ref_dZ = oracle.edge_softmax_bwd(indptr, ref_U, dU.astype(np.float64), scale)
+    Zd, dUd = torch.from_numpy(Z).cuda(), torch.from_numpy(dU).cuda()
+    U, lse = gta.gta_edge_softmax(plan, Zd, scale)
+    dZ = gta.gta_edge_softmax_bwd(plan, torch.from_numpy(ref_U.astype(np.float32)).cuda(), dUd, scale)
+    torch.cuda.synchronize()
+    assert_close("U", to_f64(U), ref_U, 1e-5)
+    assert_lse_close(to_f64(lse), ref_lse, 1e-5)
+    assert_close("dZ", to_f64(dZ), ref_dZ, 1e-5)
+    # the same through buffers that are only 4-byte aligned
+    pad = torch.empty(E * heads + 1, dtype=torch.float32, device="cuda")
+    Zu = pad[1:].view(E, heads)
+    Zu.copy_(Zd)
+    U2, lse2 = gta.gta_edge_softmax(plan, Zu, scale)
+    torch.cuda.synchronize()
+    assert_close("U (4-byte path)", to_f64(U2), ref_U, 1e-5)     # another summation order than the 16-byte path
+    assert_lse_close(to_f64(lse2), ref_lse, 1e-5)
