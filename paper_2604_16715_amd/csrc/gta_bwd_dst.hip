@@ -100,7 +100,7 @@ k_rowstat(const char* out, const char* dO, const float* lse, float2* rowstat, in
     const int lig = threadIdx.x % G;
     float d = 0.f;
     if (row < n_rows) {
-        d = Elt<T>::dot(load16(dO, row, stride, lig), load16(out, row, stride, lig));
+        d = Elt<T>::dot(load16_stream(dO, row, stride, lig), load16_stream(out, row, stride, lig));
     }
     d = head_allreduce<LH>(d);
     if (row < n_rows && lig % LH == 0)

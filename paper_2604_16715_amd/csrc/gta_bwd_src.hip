@@ -49,8 +49,8 @@ struct BwdSrcPass {
         n_heads = p.heads;
         my_lig = lig;
         if (active) {
-            kraw = load16(p.K, p.split, row, p.stride, lig);
-            vraw = load16(p.V, p.split, row, p.stride, lig);
+            kraw = load16_stream(row < p.split ? p.K.lo : p.K.hi, row, p.stride, lig);   // its owner reads it once
+            vraw = load16_stream(row < p.split ? p.V.lo : p.V.hi, row, p.stride, lig);
         }
     }
     __device__ __forceinline__ void load(const Params& p, int u, int i, int e, bool ok, int lig) {
@@ -74,7 +74,7 @@ struct BwdSrcPass {
             const float da = head_allreduce<LH>(Elt<T>::dot(gr[u], vraw));
             const float a = ok[u] ? fast_exp2(s - st[u].x) : 0.f;
             const float dz = a * (da - st[u].y);
-            if (STORE && ok[u] && my_lig % LH == 0) ds_out[(int64_t)eids[u] * n_heads + my_lig / LH] = dz;
+            if (STORE && ok[u] && my_lig % LH == 0) __builtin_nontemporal_store(dz, ds_out + (int64_t)eids[u] * n_heads + my_lig / LH);
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 f[i] = fmaf(dz, q[i], f[i]);

@@ -36,7 +36,7 @@ struct FwdPass {
         f[NV + 1] = 0.f;
         qscale = p.qscale;
         q = make_uint4(0, 0, 0, 0);
-        if (active) q = load16(p.Q, row, p.stride, lig);
+        if (active) q = load16_stream(p.Q, row, p.stride, lig);
     }
     __device__ __forceinline__ void load(const Params& p, int u, int j, int, bool ok, int lig) {
         kr[u] = make_uint4(0, 0, 0, 0);

@@ -85,8 +85,18 @@ template <> struct Elt<bf16_tag> {
 __device__ __forceinline__ uint4 load16(const char* base, int64_t row, int64_t stride, int lig) {
     return *reinterpret_cast<const uint4*>(base + row * stride + lig * 16);
 }
+// Output rows are written once and not read again by the same pass: non-temporal, so they do not
+// push gathered rows out of the caches.
 __device__ __forceinline__ void store16(char* base, int64_t row, int64_t stride, int lig, uint4 v) {
-    *reinterpret_cast<uint4*>(base + row * stride + lig * 16) = v;
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(base + row * stride + lig * 16));
+}
+// ... and a row that only its owner reads (never gathered in this pass) is loaded the same way
+__device__ __forceinline__ uint4 load16_stream(const char* base, int64_t row, int64_t stride, int lig) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + row * stride + lig * 16));
+    return make_uint4(w.x, w.y, w.z, w.w);
 }
 // rows of a two-segment source tensor
 __device__ __forceinline__ uint4 load16(const SegConst& t, int split, int row, int64_t stride, int lig) {
@@ -135,7 +145,7 @@ struct ChunkSet {
 template <class Pass>
 __device__ __forceinline__ int entry_id(const int32_t* eid, int pos, bool valid) {
     if (!Pass::kUsesEntryId || !valid || !eid) return 0;
-    return eid[pos];
+    return __builtin_nontemporal_load(eid + pos);   // read once
 }
 
 // One batch of up to 64 consecutive entries held one per lane (slot t lives in lane lane_base+t).

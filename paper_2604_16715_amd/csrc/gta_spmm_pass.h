@@ -34,7 +34,7 @@ struct SpmmPass {
         w[u] = 0.f;
         if (ok) {
             xr[u] = load16(p.X, p.split, j, p.stride, lig);
-            w[u] = p.Wt[(int64_t)e * p.heads + lig / LH];
+            w[u] = __builtin_nontemporal_load(p.Wt + (int64_t)e * p.heads + lig / LH);   // every weight is read once
         }
     }
     __device__ __forceinline__ void compute(const bool (&)[U]) {
