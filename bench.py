@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # (see profiles/), keyed by (workload, kernel); absent = not measured.
 MEASURED_TRAFFIC_BYTES: dict = {
     # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, scale factors from the copy probe
-    ("large", "bwd_src"): int((35996730 * 2.0 + 4665731 * 1.0) * 1024),
+    ("large", "bwd_src"): int((35903089 * 2.0 + 4718295 * 1.0) * 1024),
     ("partition", "bwd_src"): int((25716815 * 2.0 + 4158668 * 1.0) * 1024),
     ("skew", "bwd_src"): int((23806851 * 2.0 + 3079636 * 1.0) * 1024),
 }
