@@ -208,7 +208,7 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
             _Pragma("unroll") for (int q = 0; q < NI; ++q) {                                       \
                 int64_t row = frow0 + RPI * q + crow;                                              \
                 row = row < last_row ? row : last_row;                                             \
-                CSET[q] = *reinterpret_cast<const u32x4*>(C + row * d_out + ccol);                 \
+                CSET[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(C + row * d_out + ccol)); \
             }                                                                                      \
         }
 #define GTA_STEP(SET, CSET, STEP, ODD, AHEAD)                                                      \
@@ -246,8 +246,9 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
                 _Pragma("unroll") for (int q = 0; q < NI; ++q) {                                   \
                     int64_t row = row0 + RPI * q + crow;                                           \
                     row = row < last_row ? row : last_row;                                         \
-                    *reinterpret_cast<u32x4*>(Y + row * d_out + ccol) =                            \
-                        *reinterpret_cast<const u32x4*>(patch + (RPI * q + crow) * kPatchPitch + 8 * cunit); \
+                    __builtin_nontemporal_store(                                                   \
+                        *reinterpret_cast<const u32x4*>(patch + (RPI * q + crow) * kPatchPitch + 8 * cunit), \
+                        reinterpret_cast<u32x4*>(Y + row * d_out + ccol));                         \
                 }                                                                                  \
                 if (AHEAD) GTA_FETCH_C(CSET, s + 2, ODD)                                           \
             }                                                                                      \
@@ -373,7 +374,10 @@ k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, flo
         for (int q = 0; q < 4; ++q) {
             const int64_t r = r0 + rq * 4 + q;
             slot[q] = make_uint4(0, 0, 0, 0);
-            if (col_ok && r < rend) slot[q] = *reinterpret_cast<const uint4*>(src + r * ld + cbase);
+            if (col_ok && r < rend) {   // both operands are read once: non-temporal
+                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + r * ld + cbase));
+                slot[q] = make_uint4(v.x, v.y, v.z, v.w);
+            }
         }
     };
 #pragma unroll
