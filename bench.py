@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES: dict = {
     # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, scale factors from the copy probe
     ("large", "bwd_src"): int((35903089 * 2.0 + 4718295 * 1.0) * 1024),
-    ("partition", "bwd_src"): int((25716815 * 2.0 + 4158668 * 1.0) * 1024),
-    ("skew", "bwd_src"): int((23806851 * 2.0 + 3079636 * 1.0) * 1024),
+    ("partition", "bwd_src"): int((25576002 * 2.0 + 4332582 * 1.0) * 1024),
+    ("skew", "bwd_src"): int((23556107 * 2.0 + 3438998 * 1.0) * 1024),
 }
 
 
