@@ -8,4 +8,3 @@ from .binding import (  # noqa: F401
     gta_profile_enable, gta_profile_read, gta_version, lib_path, load_library,
     gta_sddmm, gta_edge_softmax, gta_edge_softmax_bwd, gta_spmm, gta_agp_select, gta_head_split, gta_head_merge, gta_linear, gta_linear_dw, gta_sga_layer_fwd, gta_sga_layer_bwd,
 )
-from .autograd import SGALayer, sparse_graph_attention  # noqa: F401,E402

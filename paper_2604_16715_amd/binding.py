@@ -143,6 +143,33 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise GtaError(2, f"unsupported tensor dtype {t.dtype}")
 
 
+def _need(name: str, t, shape, dtype, device):
+    """Raises GtaError unless t is a contiguous tensor of exactly this shape, dtype and device.  The C
+    ABI takes raw pointers and cannot see a mismatch, so every tensor is checked before a call."""
+    if not isinstance(t, torch.Tensor):
+        raise GtaError(1, f"{name}: expected a tensor, got {type(t).__name__}")
+    if t.device != device:
+        raise GtaError(1, f"{name}: on {t.device}, expected {device}")
+    if t.dtype != dtype:
+        raise GtaError(1, f"{name}: dtype {t.dtype}, expected {dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise GtaError(1, f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if not t.is_contiguous():
+        raise GtaError(1, f"{name}: must be contiguous")
+
+
+def _need3(name: str, t):
+    if not isinstance(t, torch.Tensor) or t.dim() != 3:
+        raise GtaError(1, f"{name}: expected a tensor [rows, heads, head_dim]")
+    return tuple(t.shape)
+
+
+def _need_all(device, dtype, **named):
+    """named: name=(tensor, shape); every tensor must have the given dtype, shape and device."""
+    for name, (t, shape) in named.items():
+        _need(name, t, shape, dtype, device)
+
+
 def gta_version() -> str:
     return load_library().gta_version().decode()
 
@@ -201,12 +228,20 @@ class Plan:
 
 
 def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pack_max_deg=0,
-                    wave_max_deg=0, hub_chunk=0, validate=False, keep_dz_min_nnz=0) -> Plan:
+                    wave_max_deg=0, hub_chunk=0, validate=True, keep_dz_min_nnz=0) -> Plan:
+    """The plan is built once per graph, so the CSR arrays are checked on the device by default
+    (validate=True): the kernels that use the plan do not bounds-check the indices."""
     lib = load_library()
+    if not isinstance(indptr, torch.Tensor) or not isinstance(indices, torch.Tensor):
+        raise GtaError(1, "indptr and indices must be tensors")
     if indptr.dtype != torch.int64 or indices.dtype != torch.int32:
         raise GtaError(1, "indptr must be int64 and indices int32")
+    if indptr.dim() != 1 or indices.dim() != 1 or indptr.numel() < 1:
+        raise GtaError(1, "indptr [n_dst + 1] and indices [nnz] must be one-dimensional")
     if not (indptr.is_cuda and indices.is_cuda and indptr.is_contiguous() and indices.is_contiguous()):
         raise GtaError(1, "graph tensors must be contiguous device tensors")
+    if indptr.device != indices.device:
+        raise GtaError(1, "indptr and indices are on different devices")
     n_dst = indptr.numel() - 1
     nnz = indices.numel()
     opts = _PlanOpts(pack_max_deg, wave_max_deg, hub_chunk, int(bool(validate)), keep_dz_min_nnz)
@@ -227,17 +262,30 @@ def gta_attn_scratch_bytes(plan: Plan, heads: int, head_dim: int, dtype_code: in
     return int(fn(plan.handle, heads, head_dim, dtype_code))
 
 
+def _attn_shapes(plan: Plan, Q, n_src=None):
+    """(n_dst, heads, head_dim), dtype code, device and the [n_src, H, D] shape, checked against the plan."""
+    n_dst, heads, head_dim = _need3("Q", Q)
+    if n_dst != plan.n_dst:
+        raise GtaError(1, f"Q has {n_dst} rows, the plan {plan.n_dst}")
+    n_src = plan.n_src if n_src is None else n_src
+    if n_src != plan.n_src:
+        raise GtaError(1, f"K / V have {n_src} rows in total, the plan {plan.n_src}")
+    return (n_dst, heads, head_dim), _dtype_code(Q), plan.indptr.device, (n_src, heads, head_dim)
+
+
 def gta_attn_fwd(plan: Plan, Q, K, V, scale: float = 0.0, out=None, lse=None):
     """out [n_dst,H,D] (dtype of Q) and lse [n_dst,H] float32."""
-    n_dst, heads, head_dim = Q.shape
-    code = _dtype_code(Q)
+    qs, code, dev, ks = _attn_shapes(plan, Q)
+    n_dst, heads, head_dim = qs
     if out is None:
-        out = torch.empty_like(Q)
+        out = torch.empty(qs, dtype=Q.dtype, device=dev)
     if lse is None:
-        lse = torch.empty((n_dst, heads), dtype=torch.float32, device=Q.device)
+        lse = torch.empty((n_dst, heads), dtype=torch.float32, device=dev)
+    _need_all(dev, Q.dtype, Q=(Q, qs), K=(K, ks), V=(V, ks), out=(out, qs))
+    _need("lse", lse, (n_dst, heads), torch.float32, dev)
     scratch = plan.scratch(heads, head_dim, code)
     _check(load_library().gta_attn_fwd(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q), _ptr(K),
-                                       _ptr(V), _ptr(out), _ptr(lse), n_dst, K.shape[0], heads, head_dim,
+                                       _ptr(V), _ptr(out), _ptr(lse), n_dst, plan.n_src, heads, head_dim,
                                        code, scale, _ptr(scratch), scratch.numel(), _stream()))
     return out, lse
 
@@ -246,29 +294,41 @@ def gta_attn_bwd(plan: Plan, Q, K, V, out, lse, dOut, scale: float = 0.0, dQ=Non
                  lean_scratch: bool = False):
     """lean_scratch=True passes the minimum scratch, which selects the backward form that keeps
     nothing per stored entry."""
-    n_dst, heads, head_dim = Q.shape
-    code = _dtype_code(Q)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(K) if dK is None else dK
-    dV = torch.empty_like(V) if dV is None else dV
+    qs, code, dev, ks = _attn_shapes(plan, Q)
+    n_dst, heads, head_dim = qs
+    dQ = torch.empty(qs, dtype=Q.dtype, device=dev) if dQ is None else dQ
+    dK = torch.empty(ks, dtype=Q.dtype, device=dev) if dK is None else dK
+    dV = torch.empty(ks, dtype=Q.dtype, device=dev) if dV is None else dV
+    _need_all(dev, Q.dtype, Q=(Q, qs), K=(K, ks), V=(V, ks), out=(out, qs), dOut=(dOut, qs), dQ=(dQ, qs),
+              dK=(dK, ks), dV=(dV, ks))
+    _need("lse", lse, (n_dst, heads), torch.float32, dev)
     scratch = plan.scratch(heads, head_dim, code, lean_scratch)
     _check(load_library().gta_attn_bwd(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q), _ptr(K),
                                        _ptr(V), _ptr(out), _ptr(lse), _ptr(dOut), _ptr(dQ), _ptr(dK), _ptr(dV),
-                                       n_dst, K.shape[0], heads, head_dim, code, scale, _ptr(scratch),
+                                       n_dst, plan.n_src, heads, head_dim, code, scale, _ptr(scratch),
                                        scratch.numel(), _stream()))
     return dQ, dK, dV
 
 
+def _halo_rows(K_local, K_halo):
+    n_local = _need3("K_local", K_local)[0]
+    return n_local, n_local + (0 if K_halo is None else _need3("K_halo", K_halo)[0])
+
+
 def gta_attn_fwd_halo(plan: Plan, Q, K_local, V_local, K_halo, V_halo, scale: float = 0.0, out=None, lse=None):
     """gta_attn_fwd with K / V given as the owned rows and a separate tensor of halo rows."""
-    n_dst, heads, head_dim = Q.shape
-    code = _dtype_code(Q)
-    n_local = K_local.shape[0]
-    n_src = n_local + (0 if K_halo is None else K_halo.shape[0])
+    n_local, n_src = _halo_rows(K_local, K_halo)
+    qs, code, dev, _ = _attn_shapes(plan, Q, n_src)
+    n_dst, heads, head_dim = qs
     if out is None:
-        out = torch.empty_like(Q)
+        out = torch.empty(qs, dtype=Q.dtype, device=dev)
     if lse is None:
-        lse = torch.empty((n_dst, heads), dtype=torch.float32, device=Q.device)
+        lse = torch.empty((n_dst, heads), dtype=torch.float32, device=dev)
+    ls, hs = (n_local, heads, head_dim), (n_src - n_local, heads, head_dim)
+    _need_all(dev, Q.dtype, Q=(Q, qs), K_local=(K_local, ls), V_local=(V_local, ls), out=(out, qs))
+    if n_src > n_local:
+        _need_all(dev, Q.dtype, K_halo=(K_halo, hs), V_halo=(V_halo, hs))
+    _need("lse", lse, (n_dst, heads), torch.float32, dev)
     scratch = plan.scratch(heads, head_dim, code)
     _check(load_library().gta_attn_fwd_halo(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q),
                                             _ptr(K_local), _ptr(V_local), _ptr(K_halo), _ptr(V_halo), n_local,
@@ -281,14 +341,19 @@ def gta_attn_bwd_halo(plan: Plan, Q, K_local, V_local, K_halo, V_halo, out, lse,
                       lean_scratch: bool = False):
     """gta_attn_bwd with K / V, dK / dV as owned rows plus halo rows; returns dQ, dK_local, dV_local,
     dK_halo, dV_halo."""
-    n_dst, heads, head_dim = Q.shape
-    code = _dtype_code(Q)
-    n_local = K_local.shape[0]
-    n_src = n_local + (0 if K_halo is None else K_halo.shape[0])
-    dQ = torch.empty_like(Q)
+    n_local, n_src = _halo_rows(K_local, K_halo)
+    qs, code, dev, _ = _attn_shapes(plan, Q, n_src)
+    n_dst, heads, head_dim = qs
+    ls, hs = (n_local, heads, head_dim), (n_src - n_local, heads, head_dim)
+    _need_all(dev, Q.dtype, Q=(Q, qs), K_local=(K_local, ls), V_local=(V_local, ls), out=(out, qs),
+              dOut=(dOut, qs))
+    if n_src > n_local:
+        _need_all(dev, Q.dtype, K_halo=(K_halo, hs), V_halo=(V_halo, hs))
+    _need("lse", lse, (n_dst, heads), torch.float32, dev)
+    dQ = torch.empty(qs, dtype=Q.dtype, device=dev)
     dK_local, dV_local = torch.empty_like(K_local), torch.empty_like(V_local)
-    dK_halo = None if K_halo is None else torch.empty_like(K_halo)
-    dV_halo = None if V_halo is None else torch.empty_like(V_halo)
+    dK_halo = None if n_src == n_local else torch.empty_like(K_halo)
+    dV_halo = None if n_src == n_local else torch.empty_like(V_halo)
     scratch = plan.scratch(heads, head_dim, code, lean_scratch)
     _check(load_library().gta_attn_bwd_halo(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q),
                                             _ptr(K_local), _ptr(V_local), _ptr(K_halo), _ptr(V_halo), n_local,
@@ -300,11 +365,16 @@ def gta_attn_bwd_halo(plan: Plan, Q, K_local, V_local, K_halo, V_halo, out, lse,
 
 def gta_attn_merge(out_a, lse_a, out_b, lse_b, out=None, lse=None):
     """Attention over the union of two disjoint entry sets from the two partial (out, lse) results."""
-    n_rows, heads, head_dim = out_a.shape
+    shape = _need3("out_a", out_a)
+    n_rows, heads, head_dim = shape
+    dev = out_a.device
     if out is None:
         out = torch.empty_like(out_a)
     if lse is None:
-        lse = torch.empty_like(lse_a)
+        lse = torch.empty((n_rows, heads), dtype=torch.float32, device=dev)
+    _need_all(dev, out_a.dtype, out_a=(out_a, shape), out_b=(out_b, shape), out=(out, shape))
+    _need_all(dev, torch.float32, lse_a=(lse_a, (n_rows, heads)), lse_b=(lse_b, (n_rows, heads)),
+              lse=(lse, (n_rows, heads)))
     _check(load_library().gta_attn_merge(_ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b), _ptr(out), _ptr(lse),
                                          n_rows, heads, head_dim, _dtype_code(out_a), _stream()))
     return out, lse
@@ -312,30 +382,45 @@ def gta_attn_merge(out_a, lse_a, out_b, lse_b, out=None, lse=None):
 
 def gta_sddmm(plan: Plan, X, Y, Z=None):
     """Z [nnz,H] float32 = per-entry, per-head dot products of X[dst] and Y[src]."""
-    n_dst, heads, head_dim = X.shape
-    code = _dtype_code(X)
+    qs, code, dev, ks = _attn_shapes(plan, X)
+    n_dst, heads, head_dim = qs
+    nnz = plan.indices.numel()
     if Z is None:
-        Z = torch.empty((plan.indices.numel(), heads), dtype=torch.float32, device=X.device)
+        Z = torch.empty((nnz, heads), dtype=torch.float32, device=dev)
+    _need_all(dev, X.dtype, X=(X, qs), Y=(Y, ks))
+    _need("Z", Z, (nnz, heads), torch.float32, dev)
     scratch = plan.scratch(heads, head_dim, code)
     _check(load_library().gta_sddmm(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(X), _ptr(Y), _ptr(Z),
-                                    n_dst, Y.shape[0], heads, head_dim, code, _ptr(scratch), scratch.numel(),
+                                    n_dst, plan.n_src, heads, head_dim, code, _ptr(scratch), scratch.numel(),
                                     _stream()))
     return Z
 
 
+def _entry_matrix(plan: Plan, name: str, t):
+    """A float32 [nnz, heads] matrix of per-entry values; returns heads."""
+    if not isinstance(t, torch.Tensor) or t.dim() != 2:
+        raise GtaError(1, f"{name}: expected a tensor [nnz, heads]")
+    _need(name, t, (plan.indices.numel(), t.shape[1]), torch.float32, plan.indptr.device)
+    return t.shape[1]
+
+
 def gta_edge_softmax(plan: Plan, Z, scale: float, U=None, lse=None):
-    heads = Z.shape[1]
+    heads = _entry_matrix(plan, "Z", Z)
     U = torch.empty_like(Z) if U is None else U
     if lse is None:
         lse = torch.empty((plan.n_dst, heads), dtype=torch.float32, device=Z.device)
+    _need("U", U, Z.shape, torch.float32, Z.device)
+    _need("lse", lse, (plan.n_dst, heads), torch.float32, Z.device)
     _check(load_library().gta_edge_softmax(plan.handle, _ptr(plan.indptr), _ptr(Z), _ptr(U), _ptr(lse),
                                            plan.n_dst, heads, scale, _stream()))
     return U, lse
 
 
 def gta_edge_softmax_bwd(plan: Plan, U, dU, scale: float, dZ=None):
-    heads = U.shape[1]
+    heads = _entry_matrix(plan, "U", U)
     dZ = torch.empty_like(U) if dZ is None else dZ
+    _need("dU", dU, U.shape, torch.float32, U.device)
+    _need("dZ", dZ, U.shape, torch.float32, U.device)
     _check(load_library().gta_edge_softmax_bwd(plan.handle, _ptr(plan.indptr), _ptr(U), _ptr(dU), _ptr(dZ),
                                                plan.n_dst, heads, scale, _stream()))
     return dZ
@@ -343,11 +428,15 @@ def gta_edge_softmax_bwd(plan: Plan, U, dU, scale: float, dZ=None):
 
 def gta_spmm(plan: Plan, W, X, transposed: bool = False, Y=None):
     """transposed=False: Y[dst] = sum W[e] X[src];  transposed=True: Y[src] = sum W[e] X[dst]."""
-    _, heads, head_dim = X.shape
+    _, heads, head_dim = _need3("X", X)
     code = _dtype_code(X)
+    dev = plan.indptr.device
+    rows_in = plan.n_dst if transposed else plan.n_src
     rows_out = plan.n_src if transposed else plan.n_dst
     if Y is None:
-        Y = torch.empty((rows_out, heads, head_dim), dtype=X.dtype, device=X.device)
+        Y = torch.empty((rows_out, heads, head_dim), dtype=X.dtype, device=dev)
+    _need_all(dev, X.dtype, X=(X, (rows_in, heads, head_dim)), Y=(Y, (rows_out, heads, head_dim)))
+    _need("W", W, (plan.indices.numel(), heads), torch.float32, dev)
     scratch = plan.scratch(heads, head_dim, code)
     _check(load_library().gta_spmm(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(W), _ptr(X), _ptr(Y),
                                    plan.n_dst, plan.n_src, heads, head_dim, code, int(bool(transposed)),
@@ -355,12 +444,23 @@ def gta_spmm(plan: Plan, W, X, transposed: bool = False, Y=None):
     return Y
 
 
+def _need2(name: str, t):
+    if not isinstance(t, torch.Tensor) or t.dim() != 2:
+        raise GtaError(1, f"{name}: expected a two-dimensional tensor")
+    return tuple(t.shape)
+
+
 def gta_linear(X, W, C=None, trans_w: bool = False, Y=None):
     """Y = X @ W (+ C) with W [d_in, d_out], or Y = X @ W.T (+ C) with W [d_out, d_in] when trans_w."""
-    n, d_in = X.shape
-    d_out = W.shape[0] if trans_w else W.shape[1]
+    n, d_in = _need2("X", X)
+    ws = _need2("W", W)
+    d_out = ws[0] if trans_w else ws[1]
+    dev = X.device
     if Y is None:
-        Y = torch.empty((n, d_out), dtype=X.dtype, device=X.device)
+        Y = torch.empty((n, d_out), dtype=X.dtype, device=dev)
+    _need_all(dev, X.dtype, X=(X, (n, d_in)), W=(W, (d_out, d_in) if trans_w else (d_in, d_out)), Y=(Y, (n, d_out)))
+    if C is not None:
+        _need("C", C, (n, d_out), X.dtype, dev)
     _check(load_library().gta_linear(_ptr(X), _ptr(W), _ptr(C), _ptr(Y), n, d_in, d_out, _dtype_code(X),
                                      int(bool(trans_w)), _stream()))
     return Y
@@ -368,13 +468,16 @@ def gta_linear(X, W, C=None, trans_w: bool = False, Y=None):
 
 def gta_linear_dw(X, dY, dW=None):
     """dW [d_in, d_out] float32 = X.T @ dY."""
-    n, d_in = X.shape
-    d_out = dY.shape[1]
+    n, d_in = _need2("X", X)
+    d_out = _need2("dY", dY)[1]
+    dev = X.device
     lib = load_library()
     if dW is None:
-        dW = torch.empty((d_in, d_out), dtype=torch.float32, device=X.device)
+        dW = torch.empty((d_in, d_out), dtype=torch.float32, device=dev)
+    _need_all(dev, X.dtype, X=(X, (n, d_in)), dY=(dY, (n, d_out)))
+    _need("dW", dW, (d_in, d_out), torch.float32, dev)
     nbytes = lib.gta_linear_dw_scratch_bytes(n, d_in, d_out)
-    scratch = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=X.device)
+    scratch = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
     _check(lib.gta_linear_dw(_ptr(X), _ptr(dY), _ptr(dW), n, d_in, d_out, _dtype_code(X), _ptr(scratch),
                              scratch.numel(), _stream()))
     return dW
@@ -390,14 +493,27 @@ def _layer_scratch(plan: Plan, heads, head_dim, code):
     return plan._scratch[key]
 
 
+def _layer_shapes(plan: Plan, X, heads: int, weights):
+    n, d = _need2("X", X)
+    if n != plan.n_dst or plan.n_src != plan.n_dst:
+        raise GtaError(1, "the layer form needs n_src == n_dst == rows of X")
+    if heads <= 0 or d % heads:
+        raise GtaError(1, f"hidden size {d} is not divisible by heads = {heads}")
+    dev = plan.indptr.device
+    _need("X", X, (n, d), X.dtype, dev)
+    for name, w in weights.items():
+        _need(name, w, (d, d), X.dtype, dev)
+    return n, d, d // heads, _dtype_code(X), dev
+
+
 def gta_sga_layer_fwd(plan: Plan, X, Wq, Wk, Wv, Wo, heads: int, scale: float = 0.0, saved=None):
     """X [n, d] -> (X' [n, d], saved) with saved = dict(Q, K, V, Y, lse) for the backward."""
-    n, d = X.shape
-    head_dim = d // heads
-    code = _dtype_code(X)
+    n, d, head_dim, code, dev = _layer_shapes(plan, X, heads, dict(Wq=Wq, Wk=Wk, Wv=Wv, Wo=Wo))
     if saved is None:
         saved = dict(Q=torch.empty_like(X), K=torch.empty_like(X), V=torch.empty_like(X), Y=torch.empty_like(X),
-                     lse=torch.empty((n, heads), dtype=torch.float32, device=X.device))
+                     lse=torch.empty((n, heads), dtype=torch.float32, device=dev))
+    _need_all(dev, X.dtype, **{k: (saved[k], (n, d)) for k in ("Q", "K", "V", "Y")})
+    _need("lse", saved["lse"], (n, heads), torch.float32, dev)
     Xout = torch.empty_like(X)
     scratch = _layer_scratch(plan, heads, head_dim, code)
     _check(load_library().gta_sga_layer_fwd(
@@ -409,12 +525,12 @@ def gta_sga_layer_fwd(plan: Plan, X, Wq, Wk, Wv, Wo, heads: int, scale: float = 
 
 def gta_sga_layer_bwd(plan: Plan, X, Wq, Wk, Wv, Wo, saved, dXout, heads: int, scale: float = 0.0):
     """Returns dX [n, d] and float32 dWq, dWk, dWv, dWo [d, d]."""
-    n, d = X.shape
-    head_dim = d // heads
-    code = _dtype_code(X)
+    n, d, head_dim, code, dev = _layer_shapes(plan, X, heads, dict(Wq=Wq, Wk=Wk, Wv=Wv, Wo=Wo))
+    _need_all(dev, X.dtype, dXout=(dXout, (n, d)), **{k: (saved[k], (n, d)) for k in ("Q", "K", "V", "Y")})
+    _need("lse", saved["lse"], (n, heads), torch.float32, dev)
     work = [torch.empty_like(X) for _ in range(3)]
     dX = torch.empty_like(X)
-    dW = [torch.empty((d, d), dtype=torch.float32, device=X.device) for _ in range(4)]
+    dW = [torch.empty((d, d), dtype=torch.float32, device=dev) for _ in range(4)]
     scratch = _layer_scratch(plan, heads, head_dim, code)
     _check(load_library().gta_sga_layer_bwd(
         plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo),
@@ -426,18 +542,25 @@ def gta_sga_layer_bwd(plan: Plan, X, Wq, Wk, Wv, Wo, saved, dXout, heads: int, s
 
 def gta_head_split(X, parts: int, S=None):
     """X [n, H, D] -> S [parts, n, H/parts, D] (block r = heads r*H/parts .. (r+1)*H/parts)."""
-    n, heads, head_dim = X.shape
+    n, heads, head_dim = _need3("X", X)
+    ss = (parts, n, max(heads // max(parts, 1), 1), head_dim)
     if S is None:
-        S = torch.empty((parts, n, max(heads // max(parts, 1), 1), head_dim), dtype=X.dtype, device=X.device)
+        S = torch.empty(ss, dtype=X.dtype, device=X.device)
+    _need("X", X, (n, heads, head_dim), X.dtype, X.device)
+    _need("S", S, ss, X.dtype, X.device)
     _check(load_library().gta_head_split(_ptr(X), _ptr(S), n, heads, head_dim, _dtype_code(X), parts, _stream()))
     return S
 
 
 def gta_head_merge(S, X=None):
     """Inverse of gta_head_split: S [parts, n, H/parts, D] -> X [n, H, D]."""
+    if not isinstance(S, torch.Tensor) or S.dim() != 4:
+        raise GtaError(1, "S: expected a tensor [parts, rows, heads/parts, head_dim]")
     parts, n, hp, head_dim = S.shape
     if X is None:
         X = torch.empty((n, hp * parts, head_dim), dtype=S.dtype, device=S.device)
+    _need("S", S, tuple(S.shape), S.dtype, S.device)
+    _need("X", X, (n, hp * parts, head_dim), S.dtype, S.device)
     _check(load_library().gta_head_merge(_ptr(S), _ptr(X), n, hp * parts, head_dim, _dtype_code(S), parts, _stream()))
     return X
 

@@ -141,8 +141,9 @@ ScratchLayout scratch_layout(const gta_plan* plan, const Shape& sh) {
     ScratchLayout L;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t G = (size_t)sh.lanes_per_row, nv = (size_t)sh.nv;
-    const size_t fwd = (size_t)plan->side[0].n_chunks * G * (nv + 2);
-    const size_t bsrc = (size_t)plan->side[1].n_chunks * G * (2 * nv);
+    // only the chunks of rows cut into several chunks leave partial results (they come first)
+    const size_t fwd = (size_t)plan->side[0].n_hub_chunks * G * (nv + 2);
+    const size_t bsrc = (size_t)plan->side[1].n_hub_chunks * G * (2 * nv);
     L.rowstat = 0;
     L.partial = up(sizeof(float2) * (size_t)plan->n_dst * (size_t)sh.heads);
     L.dS = L.partial + up(sizeof(float) * (fwd > bsrc ? fwd : bsrc)) + 256;
@@ -151,9 +152,9 @@ ScratchLayout scratch_layout(const gta_plan* plan, const Shape& sh) {
     return L;
 }
 
-gta_status check_common(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
-                        int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
-                        float* scale, void* scratch, size_t scratch_bytes, Shape* sh, ScratchLayout* sl) {
+// the checks every call that takes a plan makes, apart from its scratch buffer
+gta_status check_plan_call(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, int64_t n_dst,
+                           int64_t n_src, int heads, int head_dim, gta_dtype dtype, float* scale, Shape* sh) {
     if (!plan) return fail(GTA_ERR_INVALID_ARG, "plan is null");
     if (!indptr || (!indices && plan->nnz > 0)) return fail(GTA_ERR_INVALID_ARG, "null graph pointer");
     if (indptr != plan->indptr || indices != plan->indices)
@@ -168,6 +169,14 @@ gta_status check_common(const gta_plan* plan, const int64_t* indptr, const int32
     gta_status rc = make_shape(heads, head_dim, dtype, sh);
     if (rc != GTA_OK) return rc;
     if (!(*scale > 0.f)) *scale = 1.0f / sqrtf((float)head_dim);
+    return GTA_OK;
+}
+
+gta_status check_common(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                        int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
+                        float* scale, void* scratch, size_t scratch_bytes, Shape* sh, ScratchLayout* sl) {
+    const gta_status rc = check_plan_call(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, scale, sh);
+    if (rc != GTA_OK) return rc;
     *sl = scratch_layout(plan, *sh);
     if (!scratch) return fail(GTA_ERR_INVALID_ARG, "scratch is null");
     if (((uintptr_t)scratch & 255) != 0) return fail(GTA_ERR_INVALID_ARG, "scratch must be 256-byte aligned");
@@ -207,6 +216,33 @@ gta_status check_halo(int64_t n_src, int64_t n_local, const void* a_halo, const 
     return GTA_OK;
 }
 
+// argument checks of the forward that do not concern the scratch buffer
+gta_status check_fwd_tensors(const void* Q, const void* K, const void* V, const void* out, const float* lse,
+                             int64_t n_dst, int64_t n_local) {
+    if ((n_dst > 0 && (!Q || !out || !lse)) || (n_local > 0 && (!K || !V)))
+        return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(out))
+        return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    return GTA_OK;
+}
+
+// launches the forward; `partial` receives the partial results of the rows cut into several chunks
+gta_status run_fwd(const gta_plan* plan, const Shape& sh, const void* Q, const void* K, const void* V,
+                   const void* K_halo, const void* V_halo, int64_t n_local, void* out, float* lse, int64_t n_src,
+                   float scale, float* partial, void* stream) {
+    AttnArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = plan; a.Q = Q; a.K = K; a.V = V; a.o_out = out; a.lse_out = lse;
+    if (n_local < n_src) { a.K_halo = K_halo; a.V_halo = V_halo; a.n_local = n_local; }
+    a.partial = partial;
+    a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
+    for (int s = 0; s < sh.n_slices; ++s) {
+        const gta_status rc = launch_fwd(slice_args(a, s));
+        if (rc != GTA_OK) return rc;
+    }
+    return GTA_OK;
+}
+
 gta_status attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, const void* Q,
                     const void* K, const void* V, const void* K_halo, const void* V_halo, int64_t n_local,
                     void* out, float* lse, int64_t n_dst, int64_t n_src, int heads, int head_dim,
@@ -216,21 +252,10 @@ gta_status attn_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* 
     gta_status rc = check_common(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, &scale,
                                  scratch, scratch_bytes, &sh, &sl);
     if (rc != GTA_OK) return rc;
-    if ((n_dst > 0 && (!Q || !out || !lse)) || (n_local > 0 && (!K || !V)))
-        return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
-    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(out))
-        return fail(GTA_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    if ((rc = check_fwd_tensors(Q, K, V, out, lse, n_dst, n_local)) != GTA_OK) return rc;
     if (n_dst == 0) return GTA_OK;
-    AttnArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = plan; a.Q = Q; a.K = K; a.V = V; a.o_out = out; a.lse_out = lse;
-    if (n_local < n_src) { a.K_halo = K_halo; a.V_halo = V_halo; a.n_local = n_local; }
-    a.rowstat = reinterpret_cast<float2*>(static_cast<char*>(scratch) + sl.rowstat);
-    a.partial = reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial);
-    a.scale = scale; a.shape = sh; a.stream = static_cast<hipStream_t>(stream);
-    for (int s = 0; s < sh.n_slices; ++s)
-        if ((rc = launch_fwd(slice_args(a, s))) != GTA_OK) return rc;
-    return GTA_OK;
+    return run_fwd(plan, sh, Q, K, V, K_halo, V_halo, n_local, out, lse, n_src, scale,
+                   reinterpret_cast<float*>(static_cast<char*>(scratch) + sl.partial), stream);
 }
 
 gta_status attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices, const void* Q,

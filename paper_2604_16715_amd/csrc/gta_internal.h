@@ -25,6 +25,8 @@ struct Side {
     int64_t bin_off[GTA_NUM_CLASSES + 1] = {0};   // host copy
     int64_t class_entries[GTA_NUM_CLASSES] = {0}; // host: stored entries per degree class (key order)
     int64_t n_chunked = 0, n_hub = 0, n_chunks = 0;
+    int64_t n_hub_chunks = 0;       // chunks of the n_hub rows cut into several chunks: chunks[0 .. n_hub_chunks), the
+                                    // only ones that leave partial results
 };
 
 }  // namespace gta

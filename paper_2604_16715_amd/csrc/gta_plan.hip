@@ -403,11 +403,14 @@ struct Builder {
                            sd->bin_rows, sd->n_chunked, plan->hub_chunk, cnt);
         rc = scan(cnt, sd->chunk_ptr, sd->n_chunked + 1);
         if (rc != GTA_OK) return rc;
-        int32_t total = 0;
+        int32_t total = 0, hub_total = 0;
         GTA_HIP_TRY(hipMemcpyAsync(&total, sd->chunk_ptr + sd->n_chunked, sizeof(int32_t),
+                                   hipMemcpyDeviceToHost, st));
+        GTA_HIP_TRY(hipMemcpyAsync(&hub_total, sd->chunk_ptr + sd->n_hub, sizeof(int32_t),
                                    hipMemcpyDeviceToHost, st));
         GTA_HIP_TRY(hipStreamSynchronize(st));
         sd->n_chunks = total;
+        sd->n_hub_chunks = hub_total;
         if (sd->n_chunks > L.max_chunks[s])
             return fail(GTA_ERR_WORKSPACE, "internal: chunk bound exceeded");
         if (sd->n_chunked > 0)
