@@ -145,6 +145,26 @@ gta_status gta_attn_bwd(const gta_plan* plan, const int64_t* indptr, const int32
                         int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
                         float scale, void* scratch, size_t scratch_bytes, void* stream);
 
+/* gta_attn_fwd for callers that cannot allocate device memory and have no scratch buffer to pass:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * call allocates nothing: the partial results of the rows cut into several chunks (degree >
+ * hub_chunk) go to a fixed GTA_NOALLOC_SCRATCH_BYTES array inside the library's device image, which
+ * every GPU the library runs on holds until the process ends.  The first call on a device looks the
+ * array's device address up once (hipGetSymbolAddress, with that device current) and keeps it; make
+ * that call outside a graph capture.  Launch timing (gta_profile_enable) creates events and must be
+ * off for such callers.
+ * A graph whose split rows need more (chunks of such rows x heads x (head_dim + 2 values per
+ * 16 bytes of a head) x 4 bytes) is rejected with GTA_ERR_WORKSPACE; use gta_attn_fwd then.
+ * All calls on one GPU share that array: calls that overlap on one GPU (two streams, two threads)
+ * race on it; calls on one stream, or otherwise ordered, do not.  Nothing in it needs clearing
+ * between calls: every value read was written earlier by the same call.  Inputs, outputs, results
+ * (bitwise) and all other rules are those of gta_attn_fwd. */
+#define GTA_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+gta_status gta_attn_fwd_noalloc(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
+                                const void* Q, const void* K, const void* V, void* out, float* lse,
+                                int64_t n_dst, int64_t n_src, int heads, int head_dim, gta_dtype dtype,
+                                float scale, void* stream);
+
 /* The same two calls for a GPU whose K / V rows sit in two allocations (Section 3.1, Algorithm 1:
  * the rows it owns, and the halo rows an all-gather delivered into a receive buffer), so that no
  * concatenated copy has to be made.  Source ids 0 .. n_local-1 address K_local / V_local

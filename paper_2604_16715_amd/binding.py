@@ -74,6 +74,9 @@ def load_library():
     lib.gta_attn_fwd.restype = c_int
     lib.gta_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int,
                                  c_float, vp, c_size_t, vp]
+    lib.gta_attn_fwd_noalloc.restype = c_int
+    lib.gta_attn_fwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int, c_int, c_int,
+                                         c_float, vp]
     lib.gta_attn_bwd.restype = c_int
     lib.gta_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, c_int64, c_int64, c_int,
                                  c_int, c_int, c_float, vp, c_size_t, vp]
@@ -287,6 +290,19 @@ def gta_attn_fwd(plan: Plan, Q, K, V, scale: float = 0.0, out=None, lse=None):
     _check(load_library().gta_attn_fwd(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q), _ptr(K),
                                        _ptr(V), _ptr(out), _ptr(lse), n_dst, plan.n_src, heads, head_dim,
                                        code, scale, _ptr(scratch), scratch.numel(), _stream()))
+    return out, lse
+
+
+def gta_attn_fwd_noalloc(plan: Plan, Q, K, V, out, lse, scale: float = 0.0):
+    """gta_attn_fwd without any allocation: out [n_dst,H,D] and lse [n_dst,H] must be given, and the
+    partial results of split rows go to the library's built-in device array."""
+    qs, code, dev, ks = _attn_shapes(plan, Q)
+    n_dst, heads, head_dim = qs
+    _need_all(dev, Q.dtype, Q=(Q, qs), K=(K, ks), V=(V, ks), out=(out, qs))
+    _need("lse", lse, (n_dst, heads), torch.float32, dev)
+    _check(load_library().gta_attn_fwd_noalloc(plan.handle, _ptr(plan.indptr), _ptr(plan.indices), _ptr(Q),
+                                               _ptr(K), _ptr(V), _ptr(out), _ptr(lse), n_dst, plan.n_src, heads,
+                                               head_dim, code, scale, _stream()))
     return out, lse
 
 

@@ -348,6 +348,55 @@ extern "C" GTA_API gta_status gta_attn_bwd_halo(const gta_plan* plan, const int6
                     scratch_bytes, stream);
 }
 
+// ---------------------------------------------------------------- forward without any allocation
+// For callers that cannot allocate device memory and have none to pass for scratch: the partial
+// results of the rows cut into several chunks go to a fixed array in the library's own device image.
+// Every GPU holds its own copy of that array at its own address; the address is looked up once per
+// device, with that device current, and kept.
+namespace {
+constexpr size_t kNoallocScratchBytes = GTA_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoallocScratchBytes];
+std::mutex g_noalloc_mutex;
+void* g_noalloc_ptr[kMaxDevices] = {nullptr};
+
+// device address of g_noalloc_scratch on the current device (`device`)
+gta_status noalloc_scratch(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices)
+        return fail(GTA_ERR_UNSUPPORTED, "device id %d is outside the supported range 0..%d", device, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (!g_noalloc_ptr[device]) {
+        void* ptr = nullptr;
+        GTA_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_noalloc_scratch)));
+        if (!ptr) return fail(GTA_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_noalloc_ptr[device] = ptr;
+    }
+    *out = g_noalloc_ptr[device];
+    return GTA_OK;
+}
+}  // namespace
+
+extern "C" GTA_API gta_status gta_attn_fwd_noalloc(const gta_plan* plan, const int64_t* indptr,
+                                           const int32_t* indices, const void* Q, const void* K, const void* V,
+                                           void* out, float* lse, int64_t n_dst, int64_t n_src, int heads,
+                                           int head_dim, gta_dtype dtype, float scale, void* stream) {
+    Shape sh;
+    gta_status rc = check_plan_call(plan, indptr, indices, n_dst, n_src, heads, head_dim, dtype, &scale, &sh);
+    if (rc != GTA_OK) return rc;
+    if ((rc = check_fwd_tensors(Q, K, V, out, lse, n_dst, n_src)) != GTA_OK) return rc;
+    const size_t need = sizeof(float) * (size_t)plan->side[0].n_hub_chunks * (size_t)sh.lanes_per_row *
+                        (size_t)(sh.nv + 2);
+    if (need > kNoallocScratchBytes)
+        return fail(GTA_ERR_WORKSPACE,
+                    "the rows cut into several chunks need %zu bytes of partial results; the built-in scratch "
+                    "holds %zu (use gta_attn_fwd with caller-provided scratch)", need, kNoallocScratchBytes);
+    if (n_dst == 0) return GTA_OK;
+    void* partial = nullptr;
+    if ((rc = noalloc_scratch(plan->device, &partial)) != GTA_OK) return rc;   // plan->device is current
+    return run_fwd(plan, sh, Q, K, V, nullptr, nullptr, n_src, out, lse, n_src, scale,
+                   static_cast<float*>(partial), stream);
+}
+
 extern "C" GTA_API gta_status gta_profile_enable(int on) {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     g_profiling = on != 0;

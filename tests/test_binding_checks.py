@@ -49,6 +49,8 @@ def test_forward_mismatches_raise_before_launch():
     with pytest.raises(gta.GtaError):
         gta.gta_attn_fwd(plan, Q, K, V, out=t(6, 4, 8))
     with pytest.raises(gta.GtaError):
+        gta.gta_attn_fwd_noalloc(plan, Q, K, V, t(6, 4, 16), t(6, 3))
+    with pytest.raises(gta.GtaError):
         gta.gta_attn_fwd(plan, Q.to(torch.float16), K.to(torch.float16), V.to(torch.float16))
 
 

@@ -1,0 +1,92 @@
+"""gta_attn_fwd_noalloc (the forward for callers that cannot allocate: partial results of split rows
+go to the library's built-in device array) against gta_attn_fwd, through the C ABI with raw
+pointers.  Two calls in a row on the same GPU share that array; the second uses a smaller graph."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import gen
+from helpers import TOL, Problem, assert_close, assert_lse_close, to_f64, to_torch
+
+pytestmark = pytest.mark.gpu
+
+
+def _vp(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _both_forwards(p: Problem, plan_kwargs):
+    """(out, lse) of gta_attn_fwd and of gta_attn_fwd_noalloc on the same plan and inputs."""
+    import paper_2604_16715_amd as gta
+    lib = gta.load_library()
+    indptr = torch.from_numpy(p.indptr).cuda()
+    indices = torch.from_numpy(p.indices).cuda()
+    plan = gta.gta_plan_create(indptr, indices, p.n_src, **plan_kwargs)
+    info = plan.info()
+    assert info.n_hub[0] > 0, "the case must have rows cut into several chunks, or the scratch is unused"
+    Q, K, V = (to_torch(getattr(p, k)) for k in ("Q", "K", "V"))
+    n_dst, heads, head_dim = Q.shape
+    code = gta.binding._dtype_code(Q)
+    ref_out, ref_lse = gta.gta_attn_fwd(plan, Q, K, V)
+    out = torch.full_like(Q, float("nan"))
+    lse = torch.full((n_dst, heads), float("nan"), dtype=torch.float32, device="cuda")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    call = lambda: lib.gta_attn_fwd_noalloc(plan.handle, _vp(indptr), _vp(indices), _vp(Q), _vp(K), _vp(V),
+                                            _vp(out), _vp(lse), n_dst, p.n_src, heads, head_dim, code, 0.0, stream)
+    # the first call on a device looks the array's address up (the runtime may place the array then)
+    assert call() == 0, lib.gta_last_error().decode()
+    torch.cuda.synchronize()
+    out.fill_(float("nan"))
+    lse.fill_(float("nan"))
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    assert call() == 0, lib.gta_last_error().decode()
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free_before, "device memory shrank during the call"
+    return (ref_out, ref_lse), (out, lse), plan
+
+
+def _compare(p, ref, got):
+    tol = TOL[p.dtype]
+    # same kernels, same order of operations: the two entry points agree bitwise ...
+    assert torch.equal(ref[0].view(torch.uint8), got[0].view(torch.uint8))
+    assert torch.equal(ref[1].view(torch.int32), got[1].view(torch.int32))
+    # ... and the new one meets the oracle's bar by itself
+    out, lse = p.oracle_forward()
+    assert_close("out", to_f64(got[0]), out, tol)
+    assert_lse_close(to_f64(got[1]), lse, tol)
+
+
+def test_two_calls_in_a_row_second_smaller():
+    big = Problem.from_workload(gen.workload("mid", 2))       # fp32 [.,8,16], one hub of several thousand entries
+    small = Problem.from_workload(gen.workload("tiny", 1))    # fp32 [4096,4,16], max in-degree 385
+    kw_big = dict(wave_max_deg=64, hub_chunk=256)
+    kw_small = dict(wave_max_deg=16, hub_chunk=64)
+    print(f"noalloc: first call nnz={int(big.indptr[-1])}", flush=True)
+    ref, got, plan_big = _both_forwards(big, kw_big)
+    _compare(big, ref, got)
+    print(f"noalloc: second call nnz={int(small.indptr[-1])}", flush=True)
+    ref, got, _ = _both_forwards(small, kw_small)
+    _compare(small, ref, got)
+
+
+def test_bf16_and_size_limit():
+    import paper_2604_16715_amd as gta
+    lib = gta.load_library()
+    p = Problem.from_workload(gen.workload("large", 64))      # bf16 [.,8,32]
+    ref, got, plan = _both_forwards(p, dict(wave_max_deg=32, hub_chunk=64))
+    _compare(p, ref, got)
+    # a graph whose split rows need more than the built-in array is rejected, nothing is launched:
+    # 1024 rows x 8192 entries in chunks of 4 -> 2 M chunks x 64 lanes x 6 floats x 4 bytes = 3 GB
+    n, deg = 1024, 8192
+    indptr = torch.arange(0, (n + 1) * deg, deg, dtype=torch.int64, device="cuda")
+    indices = (torch.arange(n * deg, dtype=torch.int64, device="cuda") % n).to(torch.int32)
+    plan = gta.gta_plan_create(indptr, indices, n, wave_max_deg=4, hub_chunk=4)
+    Q = torch.zeros((n, 16, 16), dtype=torch.float32, device="cuda")
+    out, lse = torch.empty_like(Q), torch.empty((n, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(gta.GtaError) as err:
+        gta.gta_attn_fwd_noalloc(plan, Q, Q, Q, out, lse)
+    assert err.value.status == 3 and "built-in scratch" in str(err.value)
+    torch.cuda.synchronize()
