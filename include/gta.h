@@ -272,7 +272,7 @@ gta_status gta_head_merge(const void* S, void* X, int64_t n_rows, int heads, int
 /* ---- Automatic Graph Parallelism (Section 4.3, Algorithm 3).  Host arithmetic only; all pointers
  * are HOST pointers.  With k = t_iter(1) / N, every measured coefficient beta_c(i) (seconds per
  * node for strategy c on i GPUs, 2 <= i <= max_gpus) gives the term i * beta / (i - 1); the entry
- * with the smallest term that does not exceed k is selected (ties: first in table order).
+ * with the smallest term that does not exceed k is selected (ties: fewer GPUs, then first in table order).
  * *strategy = its strategy id and *gpus = i, or (-1, 1) when no entry qualifies (stay on one
  * GPU).  est_t_iter (may be NULL) receives t_iter(1)/i + beta * N for the selection (Eq. 7 with
  * alpha(i) = alpha(1)/i).  This build runs on one GPU, so the coefficients must come from elsewhere. */

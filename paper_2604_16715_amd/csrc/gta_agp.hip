@@ -22,7 +22,8 @@ extern "C" GTA_API gta_status gta_agp_select(double t_iter1, int64_t n_nodes, co
         if (s.gpus < 2 || s.gpus > max_gpus) continue;
         if (!(s.beta >= 0.0)) return fail(GTA_ERR_INVALID_ARG, "beta must be non-negative (sample %d)", i);
         const double term = (double)s.gpus * s.beta / (double)(s.gpus - 1);   // s*beta_c(s)/(s-1)
-        if (term <= k && term < best) {            // first minimum in table order wins ties
+        // smallest admissible term; ties go to fewer GPUs, then to the entry listed first
+        if (term <= k && (term < best || (term == best && s.gpus < *gpus))) {
             best = term;
             best_beta = s.beta;
             *strategy = s.strategy;

@@ -36,6 +36,7 @@ def assert_close(name, got, ref, tol):
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.all(np.isfinite(got)), f"{name}: non-finite values"
     emax, el2 = rel_errors(got, ref)
+    print(f"    {name}: max-norm rel {emax:.2e}, l2 rel {el2:.2e} (gate {tol:.0e})", flush=True)
     assert emax <= tol and el2 <= tol, f"{name}: max-norm rel {emax:.3e}, l2 rel {el2:.3e} > {tol:.1e}"
     return emax, el2
 

@@ -40,9 +40,8 @@ def test_layer_forward_backward(name, shrink, heads, head_dim):
 
 @pytest.mark.parametrize("name,shrink,heads,head_dim", [("tiny", 1, 4, 16), ("mid", 4, 8, 16)])
 def test_layer_forward_backward_f32(name, shrink, heads, head_dim):
-    """The fp32 layer (the tiny and mid workloads are fp32).  Tolerance: each of the four stages a value
-    passes through (projection, attention, projection; their gradients likewise) stays within the fp32
-    bar of 1e-5 by itself; the errors of up to four stages add, so the composite is gated at 4e-5."""
+    """The fp32 layer (the tiny and mid workloads are fp32), every tensor at the fp32 bar of 1e-5
+    (measured: 4e-7 .. 1e-6 through projection, attention and projection)."""
     import paper_2604_16715_amd as gta
     w = gen.workload(name, shrink)
     n, d = w.n_dst, heads * head_dim
@@ -59,7 +58,7 @@ def test_layer_forward_backward_f32(name, shrink, heads, head_dim):
     torch.cuda.synchronize()
     ref_out, ref_saved = layer_ref.layer_forward(w.indptr, w.indices, f64(X), *[f64(a) for a in Ws], heads)
     ref = layer_ref.layer_backward(w.indptr, w.indices, f64(X), *[f64(a) for a in Ws], heads, f64(dXout))
-    tol = 4e-5
+    tol = 1e-5
     assert_close("Q", to_f64(saved["Q"]).reshape(n, heads, head_dim), ref_saved["Q"], 1e-5)
     assert_close("Y", to_f64(saved["Y"]).reshape(n, heads, head_dim), ref_saved["Y"], tol)
     assert_close("X'", to_f64(Xout), ref_out, tol)
