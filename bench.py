@@ -21,14 +21,42 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/), keyed by (workload, kernel); absent = not measured.
-MEASURED_TRAFFIC_BYTES: dict = {
-    # (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, scale factors from the copy probe
-    ("large", "bwd_src"): int((35903089 * 2.0 + 4718295 * 1.0) * 1024),
-    ("partition", "bwd_src"): int((25576002 * 2.0 + 4332582 * 1.0) * 1024),
-    ("skew", "bwd_src"): int((23556107 * 2.0 + 3438998 * 1.0) * 1024),
-}
+PROFILE_DIR = os.path.join(ROOT, "profiles")
+
+
+def profile_counters(workload: str) -> dict:
+    """Counter readings per kernel from the committed rocprofv3 --pmc summary of this workload
+    (profiles/all_kernels_<workload>.txt, lines `counters kernel=<pass> key=value ...`): FETCH_SIZE and
+    WRITE_SIZE in KiB per dispatch, the factors a plain copy of known size gave for them on the same
+    box, and the L2 hit rate.  Empty when the workload has no summary."""
+    path = os.path.join(PROFILE_DIR, f"all_kernels_{workload}.txt")
+    table: dict = {}
+    if not os.path.exists(path):
+        return table
+    for line in open(path):
+        if not line.startswith("counters "):
+            continue
+        fields = dict(kv.split("=", 1) for kv in line.split()[1:])
+        name = fields.pop("kernel")
+        table[name] = {k: float(v) for k, v in fields.items()}
+        table[name]["source"] = os.path.relpath(path, ROOT)
+    return table
+
+
+def survey_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int):
+    """Algorithmic bytes of a pass by the scope table's per-unit figures (every entry gathers its rows,
+    streams touched once, nothing kept per entry), or None for kernels that table has no row for:
+      forward                      E (2R + 4)      + N_dst (2R + 4H + 8)
+      backward, destination-major  E (2R + 4)      + N_dst (4R + 8H + 8)
+      backward, source-major       E (2R + 8H + 4) + N_src (4R + 8)"""
+    R, H = row_bytes, heads
+    if pass_name == "fwd":
+        return entries * (2 * R + 4) + rows * (2 * R + 4 * H + 8)
+    if pass_name == "bwd_dst":
+        return entries * (2 * R + 4) + rows * (4 * R + 8 * H + 8)
+    if pass_name == "bwd_src":
+        return entries * (2 * R + 8 * H + 4) + rows * (4 * R + 8)
+    return None
 
 
 def algorithmic_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int, lean: bool) -> int:
@@ -53,28 +81,55 @@ def algorithmic_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, h
 
 
 def cpu_baseline(w, sample_edges: int) -> dict:
-    """Times the oracle (as it stands) on the first rows of the workload holding about
-    `sample_edges` entries; the sources they reference are renumbered compactly."""
+    """Times the oracle (as it stands) on the host cores: on the whole workload by default, or with
+    sample_edges > 0 on its first destination rows holding about that many entries (K and V keep all
+    their rows, so the gathers are spread as in the whole workload)."""
     import gen
     import oracle
-    n_rows = int(np.searchsorted(w.indptr, min(sample_edges, w.nnz), side="left"))
+    whole = sample_edges <= 0 or sample_edges >= w.nnz
+    n_rows = w.n_dst if whole else int(np.searchsorted(w.indptr, sample_edges, side="left"))
     n_rows = max(1, min(n_rows, w.n_dst))
     nnz = int(w.indptr[n_rows])
-    indptr = w.indptr[: n_rows + 1].copy()
-    uniq, indices = np.unique(w.indices[:nnz], return_inverse=True)
-    indices = indices.astype(np.int32)
+    indptr, indices = w.indptr[: n_rows + 1], w.indices[:nnz]
     f64 = lambda x: gen.as_f32(x).astype(np.float64)
     Q, dO = f64(w.tensor("Q")[:n_rows]), f64(w.tensor("dO")[:n_rows])
-    K, V = f64(w.tensor("K")[uniq]), f64(w.tensor("V")[uniq])
+    K, V = f64(w.tensor("K")), f64(w.tensor("V"))
     t0 = time.perf_counter()
     oracle.forward(indptr, indices, Q, K, V)
     t1 = time.perf_counter()
     oracle.backward(indptr, indices, Q, K, V, dO)
     t2 = time.perf_counter()
     cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
+    what = (f"the whole workload '{w.name}' ({w.n_dst} destination rows, {nnz} entries)" if whole else
+            f"first {n_rows} destination rows ({nnz} entries, sources over all {w.n_src} rows of K / V) of "
+            f"workload '{w.name}'")
     return {"value": nnz / (t2 - t0), "unit": "edges/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {n_rows} destination rows ({nnz} entries, {len(uniq)} distinct sources, "
-                      f"renumbered) of workload '{w.name}', fp64 forward {t1 - t0:.2f}s + backward {t2 - t1:.2f}s"}
+            "sample": f"{what}, fp64 forward {t1 - t0:.2f}s + backward {t2 - t1:.2f}s"}
+
+
+def stream_ceilings(gta, torch, dev, mib: int, reps: int, log) -> dict:
+    """GB/s of plain streaming kernels (read; copy; add) over buffers of `mib` MiB, HIP-event timed."""
+    n = mib * (1 << 18)
+    a = torch.ones(n, dtype=torch.float32, device=dev)
+    b = torch.ones(n, dtype=torch.float32, device=dev)
+    dst = torch.empty(n, dtype=torch.float32, device=dev)
+    moved = {0: 1, 1: 2, 2: 3}     # buffers touched per launch
+    out = {}
+    for mode, label in ((0, "read"), (1, "copy"), (2, "add")):
+        for _ in range(2):
+            gta.gta_stream_probe(mode, dst, a, b)
+        torch.cuda.synchronize()
+        gta.gta_profile_enable(1)
+        for _ in range(reps):
+            gta.gta_stream_probe(mode, dst, a, b)
+        torch.cuda.synchronize()
+        recs = gta.gta_profile_read(reset=True)
+        gta.gta_profile_enable(0)
+        ms = sorted(r["ms"] for r in recs)[len(recs) // 2]
+        out[label] = moved[mode] * n * 4 / (ms * 1e-3) / 1e9
+        log(f"  stream probe {label}: {ms:.3f} ms for {moved[mode]} x {mib} MiB -> {out[label]:.0f} GB/s")
+    del a, b, dst
+    return out
 
 
 def time_unfused(gta, torch, plan, Q, K, V, dO, w, steps, log) -> dict:
@@ -201,7 +256,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large", choices=["tiny", "mid", "large", "partition", "skew"])
     ap.add_argument("--shrink", type=int, default=1, help="divide the workload size (debugging)")
-    ap.add_argument("--cpu-sample-edges", type=int, default=8_000_000)
+    ap.add_argument("--cpu-sample-edges", type=int, default=0,
+                    help="time the oracle on the first rows holding about this many entries instead of on "
+                         "the whole workload (0 = whole workload)")
+    ap.add_argument("--probe-mib", type=int, default=1024,
+                    help="buffer size of the streaming probes that measure the achievable bandwidth (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pack-max-deg", type=int, default=0)
     ap.add_argument("--wave-max-deg", type=int, default=0)
@@ -263,7 +322,7 @@ def main() -> int:
     if args.copy_probe_mib > 0:   # calibration kernel for rocprofv3 --pmc runs (outside the timed region)
         src = torch.ones(args.copy_probe_mib * (1 << 18), dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
-        torch.mul(src, 1.0, out=dst)
+        gta.gta_stream_probe(1, dst, src)
         torch.cuda.synchronize()
         del src, dst
 
@@ -309,7 +368,22 @@ def main() -> int:
         log("  per-schedule launches (separate grids):")
         timed_launches(2)
     dom_name, dom = max(kernels.items(), key=lambda kv: kv[1]["ms"])
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom_name))
+    ceilings = stream_ceilings(gta, torch, dev, args.probe_mib, 5, log) if args.probe_mib > 0 else {}
+    counters = profile_counters(w.name)
+
+    def counter_fields(name):
+        c = counters.get(name)
+        if not c:
+            return None, None, None
+        traffic = int((c["fetch_kib"] * c["fetch_scale"] + c["write_kib"] * c["write_scale"]) * 1024)
+        return traffic, c.get("l2_hit_pct"), c
+    traffic, l2_hit, craw = counter_fields(dom_name)
+    # the dominant kernel by the scope table's formula (when it has a row for it) and by the bytes this
+    # implementation moves (`lean` form: the two coincide; default form: + the dZ store and its index)
+    dom_survey = survey_bytes(dom_name, dom["rows"], dom["entries"], row_bytes, w.heads)
+    dom_survey = dom["bytes"] if dom_survey is None else dom_survey
+    gbs = lambda nbytes: nbytes / (dom["avg_ms"] * 1e-3) / 1e9
+    step_gbs = total_bytes / (ms_per_step * 1e-3) / 1e9
     result = {
         "metric": "edges/sec, sparse graph attention fwd+bwd, 1 MI355X; achieved HBM GB/s",
         "value": edges_per_s, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -323,13 +397,27 @@ def main() -> int:
                    "plan_workspace_bytes": int(plan.workspace.numel()),
                    "scratch_bytes": int(plan.scratch(w.heads, w.head_dim, 1 if w.dtype == "bf16" else 0,
                                                      args.lean_scratch).numel())},
-        "hbm": {"algorithmic_bytes_per_step": total_bytes,
-                "achieved_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
-                "frac_of_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "hbm": {"algorithmic_bytes_per_step": total_bytes, "achieved_gbs": step_gbs,
+                "spec_peak_gbs": HBM_PEAK_GBS, "frac_of_peak": step_gbs / HBM_PEAK_GBS,
+                "read_ceiling_gbs": ceilings.get("read"), "copy_ceiling_gbs": ceilings.get("copy"),
+                "add_ceiling_gbs": ceilings.get("add"),
+                "note": "achieved = algorithmic bytes (every entry gathers its rows, no reuse assumed) over "
+                        "time; gathers repeated within the 256 MB Infinity Cache or L2 never reach DRAM, so "
+                        "this can exceed what a streaming kernel reaches (the *_ceiling_gbs probes, "
+                        "measured in this run)"},
         "kernels": {n: {"avg_ms": round(k["avg_ms"], 4), "gbs": round(k["gbs"], 1)} for n, k in kernels.items()},
-        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": dom["bytes"], "avg_launch_ms": dom["avg_ms"]},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": gbs(dom_survey), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbs(dom_survey) / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": dom_survey, "avg_launch_ms": dom["avg_ms"],
+                     "achieved_impl_model": gbs(dom["bytes"]), "frac_impl_model": gbs(dom["bytes"]) / HBM_PEAK_GBS,
+                     "bytes_per_launch_impl_model": dom["bytes"],
+                     "frac_of_read_ceiling": gbs(dom_survey) / ceilings["read"] if ceilings else None,
+                     "l2_hit_pct": l2_hit,
+                     "traffic_note": None if craw is None else
+                     f"L2<->fabric bytes per launch (Infinity-Cache hits included; no gfx950 counter separates "
+                     f"them from DRAM): (FETCH_SIZE {craw['fetch_kib']:.0f} KiB x {craw['fetch_scale']} + WRITE_SIZE "
+                     f"{craw['write_kib']:.0f} KiB x {craw['write_scale']}) x 1024, factors from a copy of known "
+                     f"size; from {craw['source']}"},
     }
     if args.unfused:
         result["unfused"] = time_unfused(gta, torch, plan, Q, K, V, dO, w, args.steps, log)

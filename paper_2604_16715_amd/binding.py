@@ -115,6 +115,8 @@ def load_library():
     lib.gta_agp_select.restype = c_int
     lib.gta_agp_select.argtypes = [ctypes.c_double, c_int64, POINTER(_AgpSample), c_int, c_int, POINTER(c_int),
                                    POINTER(c_int), POINTER(ctypes.c_double)]
+    lib.gta_stream_probe.restype = c_int
+    lib.gta_stream_probe.argtypes = [c_int, vp, vp, vp, c_size_t, vp]
     lib.gta_profile_enable.restype = c_int
     lib.gta_profile_enable.argtypes = [c_int]
     lib.gta_profile_read.restype = c_int
@@ -589,6 +591,16 @@ def gta_agp_select(t_iter1: float, n_nodes: int, samples, max_gpus: int):
     _check(load_library().gta_agp_select(t_iter1, n_nodes, arr, len(samples), max_gpus, ctypes.byref(strategy),
                                          ctypes.byref(gpus), ctypes.byref(est)))
     return strategy.value, gpus.value, est.value
+
+
+def gta_stream_probe(mode: int, dst, a, b=None):
+    """mode 0: read a; 1: dst = a; 2: dst = a + b (float32 tensors of equal size, multiples of 16 bytes)."""
+    n = a.numel()
+    for name, t in (("dst", dst), ("a", a)) + ((("b", b),) if mode == 2 else ()):
+        _need(name, t, (n,) if mode or name != "dst" else tuple(t.shape), torch.float32, a.device)
+    if mode == 0 and dst.numel() < 4:
+        raise GtaError(1, "dst needs at least 16 bytes")
+    _check(load_library().gta_stream_probe(int(mode), _ptr(dst), _ptr(a), _ptr(b), n * 4, _stream()))
 
 
 def gta_profile_enable(on):

@@ -176,3 +176,38 @@ def sampled_parity(p: Problem, name: str, seed: int, nnz: int, dst_count: int = 
     kdk = (K_t * dK_t.double()).sum(dim=(0, 2))
     mag = (Q_t * dQ_t.double()).abs().sum(dim=(0, 2))
     assert torch.all((qdq - kdk).abs() <= tol * mag), "sum q.dQ != sum k.dK"
+
+
+def whole_parity(p: Problem, name: str, nnz: int):
+    """GPU forward + backward on the whole problem in the benchmark's launch configuration (default
+    plan), the oracle on the whole problem too; all five outputs compared element by element."""
+    import time
+    tol = TOL[p.dtype]
+    print(f"whole-tensor case {name}: n_dst={p.n_dst} n_src={p.n_src} nnz={nnz}; GPU fwd+bwd", flush=True)
+    res = run_gpu(p, plan_kwargs=dict(keep_dz_min_nnz=0))
+    info = res["plan"].info()
+    print(f"whole-tensor case {name}: plan has {int(info.n_chunked[0])}/{int(info.n_chunked[1])} chunked rows, "
+          f"{int(info.n_hub[0])}/{int(info.n_hub[1])} split rows (dst/src side); widening inputs", flush=True)
+    Q, K, V, dO = (p.f64(k) for k in ("Q", "K", "V", "dO"))
+    t0 = time.perf_counter()
+    out, lse = oracle.forward(p.indptr, p.indices, Q, K, V)
+    print(f"whole-tensor case {name}: oracle forward {time.perf_counter() - t0:.1f}s", flush=True)
+    assert_close("out", res.pop("out"), out, tol)
+    assert_lse_close(res.pop("lse"), lse, tol)
+    empty = np.diff(p.indptr) == 0
+    del out, lse
+    t0 = time.perf_counter()
+    dQ, dK, dV = oracle.backward(p.indptr, p.indices, Q, K, V, dO)
+    print(f"whole-tensor case {name}: oracle backward {time.perf_counter() - t0:.1f}s", flush=True)
+    del Q, K, V, dO
+    got = res.pop("dQ")
+    assert np.all(got[empty] == 0.0)
+    assert_close("dQ", got, dQ, tol)
+    del got, dQ
+    unused = np.ones(p.n_src, dtype=bool)
+    unused[p.indices] = False
+    for key, ref in (("dK", dK), ("dV", dV)):
+        got = res.pop(key)
+        assert np.all(got[unused] == 0.0)
+        assert_close(key, got, ref, tol)
+        del got
