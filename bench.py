@@ -256,6 +256,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large", choices=["tiny", "mid", "large", "partition", "skew"])
     ap.add_argument("--shrink", type=int, default=1, help="divide the workload size (debugging)")
+    ap.add_argument("--heads", type=int, default=0,
+                    help="run the workload's graph with this many heads instead of its own (experiments)")
+    ap.add_argument("--head-dim", type=int, default=0, help="likewise for the head dimension")
     ap.add_argument("--cpu-sample-edges", type=int, default=0,
                     help="time the oracle on the first rows holding about this many entries instead of on "
                          "the whole workload (0 = whole workload)")
@@ -292,6 +295,9 @@ def main() -> int:
 
     t0 = time.perf_counter()
     w = gen.workload(args.workload, args.shrink)
+    if args.heads > 0 or args.head_dim > 0:   # same graph, other tensor shape: no longer the named workload
+        w.heads, w.head_dim = args.heads or w.heads, args.head_dim or w.head_dim
+        w.name = f"{w.name}[{w.heads}x{w.head_dim}]"
     host = {k: w.tensor(k) for k in ("Q", "K", "V", "dO")}
     log(f"generated {w.name}: n_dst={w.n_dst} n_src={w.n_src} nnz={w.nnz} in {time.perf_counter() - t0:.1f}s")
 
@@ -348,6 +354,7 @@ def main() -> int:
         records = gta.gta_profile_read(reset=True)
         gta.gta_profile_enable(0)
         table: dict = {}
+        lean = any(r["name"].startswith("bwd_dst") for r in records)   # the form the library actually ran
         for r in records:
             k = table.setdefault(r["name"], {"ms": 0.0, "launches": 0, "rows": r["rows"], "entries": r["entries"]})
             k["ms"] += r["ms"]
@@ -356,7 +363,7 @@ def main() -> int:
             k["avg_ms"] = k["ms"] / k["launches"]
             parts = name.split(".")
             k["bytes"] = 0 if parts[-1] == "merge" else algorithmic_bytes(parts[0], k["rows"], k["entries"],
-                                                                          row_bytes, w.heads, args.lean_scratch)
+                                                                          row_bytes, w.heads, lean)
             k["gbs"] = k["bytes"] / (k["avg_ms"] * 1e-3) / 1e9 if k["avg_ms"] > 0 else 0.0
             log(f"  {name:16s} {k['avg_ms']:9.3f} ms  rows={k['rows']:9d} entries={k['entries']:10d}  "
                 f"{k['bytes'] / 1e9:8.3f} GB  {k['gbs']:8.1f} GB/s")
@@ -391,7 +398,7 @@ def main() -> int:
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "recipe": w.recipe, "n_dst": w.n_dst, "n_src": w.n_src, "nnz": w.nnz,
                    "heads": w.heads, "head_dim": w.head_dim, "accumulate": "f32",
-                   "backward": "recompute-per-entry" if args.lean_scratch else "dZ-kept-per-entry",
+                   "backward": "recompute-per-entry" if "bwd_dst" in kernels else "dZ-kept-per-entry",
                    "plan_ms": plan_ms, "wave_max_deg": int(plan.info().wave_max_deg),
                    "hub_chunk": int(plan.info().hub_chunk),
                    "plan_workspace_bytes": int(plan.workspace.numel()),

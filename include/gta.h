@@ -124,7 +124,9 @@ gta_status gta_plan_export_transpose(const gta_plan* plan, int64_t* t_indptr, in
  *                              backward gather three rows per entry instead of four.
  * gta_attn_scratch_bytes_min : smallest size accepted.  With less than the recommended size the
  *                              backward keeps nothing per entry and recomputes dZ in both of its
- *                              passes (same results up to rounding, about 20 % slower).           */
+ *                              passes (same results up to rounding, about 20 % slower).
+ * For rows (head slices) of up to 128 bytes the two sizes are equal: there the recomputing form is
+ * the faster one and is always used.                                                              */
 size_t gta_attn_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
 size_t gta_attn_scratch_bytes_min(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
 
