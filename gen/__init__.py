@@ -15,7 +15,12 @@ from dataclasses import dataclass, field
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libgraphgen.so")
+# SGA_SANITIZE=1 selects a host build with AddressSanitizer + UndefinedBehaviorSanitizer in its own
+# file (run python with the ASan runtime preloaded: LD_PRELOAD=$(g++ -print-file-name=libasan.so))
+_SANITIZE = os.environ.get("SGA_SANITIZE", "") == "1"
+_LIB_PATH = os.path.join(_HERE, "libgraphgen_san.so" if _SANITIZE else "libgraphgen.so")
+_CXXFLAGS = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
+             if _SANITIZE else ["-O2"])
 _lib = None
 
 BASE_SEED = 0x260416715
@@ -28,7 +33,7 @@ def build(force: bool = True) -> str:
     src = os.path.join(_HERE, "graphgen.cpp")
     if force or not os.path.exists(_LIB_PATH):
         subprocess.check_call(
-            ["g++", "-O2", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", _LIB_PATH, src]
+            ["g++", *_CXXFLAGS, "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", _LIB_PATH, src]
         )
     return _LIB_PATH
 

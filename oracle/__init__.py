@@ -16,7 +16,12 @@ import numpy as np
 from . import plan_ref  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsga_oracle.so")
+# SGA_SANITIZE=1 selects a host build with AddressSanitizer + UndefinedBehaviorSanitizer in its own
+# file (run python with the ASan runtime preloaded: LD_PRELOAD=$(g++ -print-file-name=libasan.so))
+_SANITIZE = os.environ.get("SGA_SANITIZE", "") == "1"
+_LIB_PATH = os.path.join(_HERE, "libsga_oracle_san.so" if _SANITIZE else "libsga_oracle.so")
+_CXXFLAGS = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
+             if _SANITIZE else ["-O2"])
 _lib = None
 
 
@@ -24,7 +29,7 @@ def build(force: bool = True) -> str:
     src = os.path.join(_HERE, "sga_oracle.cpp")
     if force or not os.path.exists(_LIB_PATH):
         subprocess.check_call(
-            ["g++", "-O2", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", _LIB_PATH, src]
+            ["g++", *_CXXFLAGS, "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", _LIB_PATH, src]
         )
     return _LIB_PATH
 
