@@ -228,17 +228,21 @@ def time_layer(gta, torch, plan, w, steps, log) -> dict:
         k = agg.setdefault(r["name"], {"ms": 0.0, "calls": 0})
         k["ms"] += r["ms"]
         k["calls"] += 1
-    flops = 2.0 * n * d * d
-    dense_bytes = {"linear_nn": n * d * el * 2, "linear_nt": n * d * el * 2, "linear_dw": n * d * el * 2}
+    flops = 2.0 * n * d * d     # one n x d x d product
+    tensor = n * d * el         # bytes of one [n, d] tensor
+    # (products, tensors moved) per launch: every operand read once, every result written once
+    dense = {"linear_nn": (1, 2), "linear_nt": (1, 2), "linear_dw": (1, 2),
+             "proj_1to3": (3, 4), "proj_1to1+C": (1, 3), "proj_1to1": (1, 2), "proj_4to1": (4, 5)}
     ops = {}
     dense_ms = 0.0
     for name, k in agg.items():
         avg = k["ms"] / k["calls"]
         entry = {"avg_ms": round(avg, 4), "calls_per_step": k["calls"] // steps}
-        if name in dense_bytes:
-            entry["tflops"] = round(flops / (avg * 1e-3) / 1e12, 1)
-            entry["gbs"] = round(dense_bytes[name] / (avg * 1e-3) / 1e9, 1)
-        if name.startswith("linear"):
+        if name in dense:
+            products, tensors = dense[name]
+            entry["tflops"] = round(products * flops / (avg * 1e-3) / 1e12, 1)
+            entry["gbs"] = round(tensors * tensor / (avg * 1e-3) / 1e9, 1)
+        if name.startswith("linear") or name.startswith("proj"):
             dense_ms += k["ms"] / steps
         ops[name] = entry
         log(f"  layer {name:20s} {avg:9.3f} ms per call x{entry['calls_per_step']}  {entry.get('tflops', '')} TFLOP/s {entry.get('gbs', '')} GB/s")

@@ -241,6 +241,20 @@ size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d_out);
 gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in, int d_out,
                          gta_dtype dtype, void* scratch, size_t scratch_bytes, void* stream);
 
+/* Several projections that share operands, in one launch (bfloat16, d in {64, 128, 256}):
+ *     Y[po][n, d] = sum_{pi < p_in} X[pi][n, d] * op(W[po * p_in + pi]) (+ C[po])      for po < p_out
+ * with op as in gta_linear (trans_w = 0: W is [d, d] input x output; 1: output x input), fp32
+ * accumulation over all p_in products and ONE rounding.  Every X[pi] is read from memory once, also
+ * when several outputs use it, and every Y[po] is written once.  Supported groupings: (p_in, p_out) =
+ * (1, 1) with or without addends, (1, 3) (Eq. 3: Q, K, V from one read of X) and (4, 1) (the input
+ * gradient dX = dX' W_o^T + dQ W_Q^T + dK W_K^T + dV W_V^T) without.  X, W, C (NULL, or p_out
+ * non-null addends), Y are HOST arrays of device pointers; no output may alias an input or addend.
+ * scratch (device, 256-byte aligned): gta_linear_group_scratch_bytes, used for the repacked weights. */
+size_t gta_linear_group_scratch_bytes(int d, int p_in, int p_out);
+gta_status gta_linear_group(const void* const* X, int p_in, const void* const* W, int p_out,
+                            const void* const* C, void* const* Y, int64_t n, int d, gta_dtype dtype,
+                            int trans_w, void* scratch, size_t scratch_bytes, void* stream);
+
 /* ---- One Sparse Graph Attention layer (Eq. 3-5) on one GPU with n_src == n_dst == n, bfloat16 or fp32:
  *   Q,K,V = X W_Q, X W_K, X W_V;   Y = attention(Q,K,V);   X' = X W_o + Y.
  * X, Q, K, V, Y, X' are [n, d] = [n, heads, head_dim]; weights are [d, d] (input x output).

@@ -106,6 +106,10 @@ def load_library():
     lib.gta_linear_dw_scratch_bytes.argtypes = [c_int64, c_int, c_int]
     lib.gta_linear_dw.restype = c_int
     lib.gta_linear_dw.argtypes = [vp, vp, vp, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
+    lib.gta_linear_group_scratch_bytes.restype = c_size_t
+    lib.gta_linear_group_scratch_bytes.argtypes = [c_int, c_int, c_int]
+    lib.gta_linear_group.restype = c_int
+    lib.gta_linear_group.argtypes = [vp, c_int, vp, c_int, vp, vp, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
     lib.gta_sga_layer_scratch_bytes.restype = c_size_t
     lib.gta_sga_layer_scratch_bytes.argtypes = [vp, c_int, c_int, c_int]
     lib.gta_sga_layer_fwd.restype = c_int
@@ -499,6 +503,41 @@ def gta_linear_dw(X, dY, dW=None):
     _check(lib.gta_linear_dw(_ptr(X), _ptr(dY), _ptr(dW), n, d_in, d_out, _dtype_code(X), _ptr(scratch),
                              scratch.numel(), _stream()))
     return dW
+
+
+def gta_linear_group(Xs, Ws, Cs=None, trans_w: bool = False, Ys=None):
+    """Ys[po] = sum_pi Xs[pi] @ op(Ws[po * len(Xs) + pi]) (+ Cs[po]); bfloat16 [n, d] tensors, d in {64, 128, 256}."""
+    Xs, Ws = list(Xs), list(Ws)
+    p_in = len(Xs)
+    if p_in == 0 or len(Ws) % p_in:
+        raise GtaError(1, "the number of weights must be a multiple of the number of inputs")
+    p_out = len(Ws) // p_in
+    n, d = _need2("X[0]", Xs[0])
+    dev, dt = Xs[0].device, Xs[0].dtype
+    if Ys is None:
+        Ys = [torch.empty((n, d), dtype=dt, device=dev) for _ in range(p_out)]
+    Ys = list(Ys)
+    if len(Ys) != p_out or (Cs is not None and len(Cs) != p_out):
+        raise GtaError(1, "one output (and addend) per group of weights")
+    for i, t in enumerate(Xs):
+        _need(f"X[{i}]", t, (n, d), dt, dev)
+    for i, t in enumerate(Ws):
+        _need(f"W[{i}]", t, (d, d), dt, dev)
+    for i, t in enumerate(Ys):
+        _need(f"Y[{i}]", t, (n, d), dt, dev)
+    for i, t in enumerate(Cs or []):
+        _need(f"C[{i}]", t, (n, d), dt, dev)
+    inputs = {t.data_ptr() for t in Xs + list(Cs or [])}
+    if any(y.data_ptr() in inputs for y in Ys):
+        raise GtaError(1, "an output aliases an input or addend")
+    lib = load_library()
+    arr = lambda ts: (c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+    nbytes = lib.gta_linear_group_scratch_bytes(d, p_in, p_out)
+    scratch = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    _check(lib.gta_linear_group(arr(Xs), p_in, arr(Ws), p_out, arr(list(Cs)) if Cs is not None else None, arr(Ys),
+                                n, d, _dtype_code(Xs[0]), int(bool(trans_w)), _ptr(scratch), scratch.numel(),
+                                _stream()))
+    return Ys
 
 
 def _layer_scratch(plan: Plan, heads, head_dim, code):

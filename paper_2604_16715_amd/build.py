@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "libgta.so")
-SOURCES = ["gta_api.hip", "gta_plan.hip", "gta_fwd.hip", "gta_bwd_dst.hip", "gta_bwd_src.hip", "gta_ops.hip", "gta_agp.hip", "gta_layout.hip", "gta_merge.hip", "gta_linear.hip", "gta_linear_f32.hip", "gta_layer.hip", "gta_probe.hip"]
+SOURCES = ["gta_api.hip", "gta_plan.hip", "gta_fwd.hip", "gta_bwd_dst.hip", "gta_bwd_src.hip", "gta_ops.hip", "gta_agp.hip", "gta_layout.hip", "gta_merge.hip", "gta_linear.hip", "gta_linear_f32.hip", "gta_layer.hip", "gta_probe.hip", "gta_proj.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

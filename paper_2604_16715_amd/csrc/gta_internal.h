@@ -143,6 +143,13 @@ gta_status launch_bwd_src(const AttnArgs& a);   // stores dS when a.dS is set
 gta_status launch_rowstat(const AttnArgs& a);   // (lse * log2 e, dY_i . Y_i) per (row, head)
 gta_status launch_bwd_dq(const AttnArgs& a);    // dQ = scale * dS K over the stored dS
 
+// grouped projections Y_po = sum_pi X_pi op(W[po][pi]) (+ C_po): bf16, d in {64, 128, 256}
+bool proj_group_supported(int d, gta_dtype dtype);
+size_t proj_group_scratch_bytes(int d, int mats);
+gta_status proj_group(const void* const* X, int p_in, const void* const* W, int p_out, const void* const* C,
+                      void* const* Y, int64_t n, int d, int trans_w, void* scratch, size_t scratch_bytes,
+                      hipStream_t st);
+
 // fp32 forms of the dense projections (the bf16 forms live with their entry points)
 gta_status launch_linear_f32(const float* X, const float* W, const float* C, float* Y, int64_t n, int d_in,
                              int d_out, int trans_w, hipStream_t st);

@@ -21,13 +21,26 @@ gta_status check_layer(const gta_plan* plan, int64_t n, int heads, int head_dim,
 }
 }  // namespace
 
-extern "C" GTA_API size_t gta_sga_layer_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype) {
-    if (!plan) return 0;
+namespace {
+// Layer scratch: [attention scratch | weight-gradient partials] (whichever is larger; never in use at the
+// same time), then the repacked weights of the grouped projections (bfloat16 layers with d in {64, 128, 256}).
+struct LayerScratch { size_t shared, pack, total; };
+LayerScratch layer_scratch(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype) {
+    LayerScratch L{0, 0, 0};
     const size_t attn = gta_attn_scratch_bytes(plan, heads, head_dim, dtype);
-    if (attn == 0) return 0;
+    if (attn == 0) return L;
     const int d = heads * head_dim;
     const size_t dw = gta_linear_dw_scratch_bytes(plan->n_dst, d, d);
-    return attn > dw ? attn : dw;
+    L.shared = ((attn > dw ? attn : dw) + 255) & ~(size_t)255;
+    L.pack = proj_group_supported(d, dtype) ? proj_group_scratch_bytes(d, 4) : 0;
+    L.total = L.shared + L.pack;
+    return L;
+}
+}  // namespace
+
+extern "C" GTA_API size_t gta_sga_layer_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype) {
+    if (!plan) return 0;
+    return layer_scratch(plan, heads, head_dim, dtype).total;
 }
 
 extern "C" GTA_API gta_status gta_sga_layer_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
@@ -38,6 +51,24 @@ extern "C" GTA_API gta_status gta_sga_layer_fwd(const gta_plan* plan, const int6
     gta_status rc = check_layer(plan, n, heads, head_dim, dtype);
     if (rc != GTA_OK) return rc;
     const int d = heads * head_dim;
+    const LayerScratch L = layer_scratch(plan, heads, head_dim, dtype);
+    if (L.total == 0) return fail(GTA_ERR_UNSUPPORTED, "unsupported shape for the layer form");
+    if (!scratch || scratch_bytes < L.total)
+        return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, L.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (L.pack > 0) {
+        // Q, K, V from one read of X (Eq. 3)
+        void* pack = static_cast<char*>(scratch) + L.shared;
+        const void* xs[1] = {X};
+        const void* wqkv[3] = {Wq, Wk, Wv};
+        void* qkv[3] = {Q, K, V};
+        if ((rc = proj_group(xs, 1, wqkv, 3, nullptr, qkv, n, d, 0, pack, L.pack, st)) != GTA_OK) return rc;
+        if ((rc = gta_attn_fwd(plan, indptr, indices, Q, K, V, Y, lse, n, n, heads, head_dim, dtype, scale, scratch,
+                               L.shared, stream)) != GTA_OK)
+            return rc;
+        // one product with an addend: the single-projection kernel is the faster of the two forms
+        return gta_linear(X, Wo, Y, Xout, n, d, d, dtype, 0, stream);
+    }
     if ((rc = gta_linear(X, Wq, nullptr, Q, n, d, d, dtype, 0, stream)) != GTA_OK) return rc;
     if ((rc = gta_linear(X, Wk, nullptr, K, n, d, d, dtype, 0, stream)) != GTA_OK) return rc;
     if ((rc = gta_linear(X, Wv, nullptr, V, n, d, d, dtype, 0, stream)) != GTA_OK) return rc;
@@ -57,18 +88,27 @@ extern "C" GTA_API gta_status gta_sga_layer_bwd(const gta_plan* plan, const int6
     gta_status rc = check_layer(plan, n, heads, head_dim, dtype);
     if (rc != GTA_OK) return rc;
     const int d = heads * head_dim;
-    if (scratch_bytes < gta_sga_layer_scratch_bytes(plan, heads, head_dim, dtype) &&
-        scratch_bytes < gta_linear_dw_scratch_bytes(n, d, d))
-        return fail(GTA_ERR_WORKSPACE, "scratch too small for the weight gradients");
+    const LayerScratch L = layer_scratch(plan, heads, head_dim, dtype);
+    if (L.total == 0) return fail(GTA_ERR_UNSUPPORTED, "unsupported shape for the layer form");
+    if (!scratch || scratch_bytes < L.total)
+        return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, L.total);
     // X' = X W_o + Y:  dY = dX',  dW_o = X^T dX',  dX = dX' W_o^T
     if ((rc = gta_attn_bwd(plan, indptr, indices, Q, K, V, Y, lse, dXout, dQ, dK, dV, n, n, heads, head_dim, dtype,
-                           scale, scratch, scratch_bytes, stream)) != GTA_OK)
+                           scale, scratch, L.shared, stream)) != GTA_OK)
         return rc;
-    if ((rc = gta_linear_dw(X, dXout, dWo, n, d, d, dtype, scratch, scratch_bytes, stream)) != GTA_OK) return rc;
-    if ((rc = gta_linear_dw(X, dQ, dWq, n, d, d, dtype, scratch, scratch_bytes, stream)) != GTA_OK) return rc;
-    if ((rc = gta_linear_dw(X, dK, dWk, n, d, d, dtype, scratch, scratch_bytes, stream)) != GTA_OK) return rc;
-    if ((rc = gta_linear_dw(X, dV, dWv, n, d, d, dtype, scratch, scratch_bytes, stream)) != GTA_OK) return rc;
-    // dX = dX' W_o^T + dQ W_Q^T + dK W_K^T + dV W_V^T, accumulated through the addend (in place)
+    if ((rc = gta_linear_dw(X, dXout, dWo, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
+    if ((rc = gta_linear_dw(X, dQ, dWq, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
+    if ((rc = gta_linear_dw(X, dK, dWk, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
+    if ((rc = gta_linear_dw(X, dV, dWv, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
+    if (L.pack > 0) {
+        // dX = dX' W_o^T + dQ W_Q^T + dK W_K^T + dV W_V^T: one kernel, summed in fp32, rounded once
+        const void* ins[4] = {dXout, dQ, dK, dV};
+        const void* ws[4] = {Wo, Wq, Wk, Wv};
+        void* out[1] = {dX};
+        return proj_group(ins, 4, ws, 1, nullptr, out, n, d, 1, static_cast<char*>(scratch) + L.shared, L.pack,
+                          static_cast<hipStream_t>(stream));
+    }
+    // other shapes: accumulated through the addend (in place), rounded to the tensor type after each product
     if ((rc = gta_linear(dXout, Wo, nullptr, dX, n, d, d, dtype, 1, stream)) != GTA_OK) return rc;
     if ((rc = gta_linear(dQ, Wq, dX, dX, n, d, d, dtype, 1, stream)) != GTA_OK) return rc;
     if ((rc = gta_linear(dK, Wk, dX, dX, n, d, d, dtype, 1, stream)) != GTA_OK) return rc;

@@ -121,3 +121,53 @@ def test_linear_weight_gradient_f32(n, d_in, d_out):
     got = gta.gta_linear_dw(to_torch(X), to_torch(dY))
     assert_close("X^T dY", to_f64(got), dense_ref.linear_dw(X.astype(np.float64), dY.astype(np.float64)), F32_TOL)
     assert torch.equal(got, gta.gta_linear_dw(to_torch(X), to_torch(dY)))   # fixed summation order
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+@pytest.mark.parametrize("n", [1, 127, 129, 1000, 40001, 150001])
+def test_linear_group(n, d):
+    """Grouped projections (one launch, every input read once): Q, K, V from one X; a projection with
+    addend; the four-term input gradient accumulated in fp32 and rounded once."""
+    import paper_2604_16715_amd as gta
+    print(f"linear_group case n={n} d={d}", flush=True)
+    Xs = [bf16_matrix(n, d, 7, 20 + i) for i in range(4)]
+    Ws = [bf16_matrix(d, d, 7, 30 + i, 0.125) for i in range(4)]
+    C = bf16_matrix(n, d, 7, 40)
+    f = lambda a: gen.bf16_bits_to_f32(a).astype(np.float64)
+    Xd, Wd, Cd = [to_torch(a) for a in Xs], [to_torch(a) for a in Ws], to_torch(C)
+    # 1 -> 3 (Eq. 3)
+    Q, K, V = gta.gta_linear_group([Xd[0]], Wd[:3])
+    for name, got, W in zip("QKV", (Q, K, V), Ws[:3]):
+        assert_close(name, to_f64(got), dense_ref.linear(f(Xs[0]), f(W)), 2e-2)
+    # ... bitwise the single projection's result (same products, same order, one rounding)
+    assert torch.equal(K.view(torch.int16), gta.gta_linear(Xd[0], Wd[1]).view(torch.int16))
+    # 1 -> 1 with and without addend (Eq. 5), both weight storage orders
+    (Y,) = gta.gta_linear_group([Xd[1]], [Wd[3]], [Cd])
+    assert_close("X W + C", to_f64(Y), dense_ref.linear(f(Xs[1]), f(Ws[3]), f(C)), 2e-2)
+    (Yt,) = gta.gta_linear_group([Xd[1]], [to_torch(np.ascontiguousarray(Ws[3].T))], [Cd], trans_w=True)
+    assert torch.equal(Y.view(torch.int16), Yt.view(torch.int16))
+    (Y0,) = gta.gta_linear_group([Xd[2]], [Wd[0]])
+    assert_close("X W", to_f64(Y0), dense_ref.linear(f(Xs[2]), f(Ws[0])), 2e-2)
+    # 4 -> 1: dX = sum_p X_p W_p^T, against the float64 sum (error of ONE bf16 rounding: well inside 2e-2)
+    (dX,) = gta.gta_linear_group(Xd, Wd, trans_w=True)
+    ref = sum(dense_ref.linear(f(x), f(w), trans_w=True) for x, w in zip(Xs, Ws))
+    emax, _ = assert_close("dX", to_f64(dX), ref, 2e-2)
+    assert emax < 4e-3   # a single rounding to bf16 (2^-9 relative) of values up to max|ref|
+    torch.cuda.synchronize()
+
+
+def test_linear_group_rejects_unsupported():
+    import paper_2604_16715_amd as gta
+    X = torch.zeros((8, 96), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((96, 96), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_group([X], [W])                     # d = 96
+    X = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_group([X, X], [W, W])               # 2 -> 1 is not an instantiated grouping
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_group([X], [W], Ys=[X])             # output aliases the input
+    Xf = torch.zeros((8, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_group([Xf], [W.float()])            # bfloat16 only
