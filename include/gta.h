@@ -260,7 +260,9 @@ gta_status gta_linear_group(const void* const* X, int p_in, const void* const* W
  * X, Q, K, V, Y, X' are [n, d] = [n, heads, head_dim]; weights are [d, d] (input x output).
  * Forward writes Q, K, V, Y, lse (kept for the backward) and Xout.  Backward takes dXout and writes
  * dX [n, d], the weight gradients dW_* (float [d, d]) and uses dQ, dK, dV [n, d] as work buffers.
- * dX accumulates four products through the tensor type (rounded after each).  scratch:
+ * bfloat16 layers with d in {64, 128, 256} compute Q, K, V in one launch (X read once) and dX as one
+ * four-term sum in fp32, rounded once (gta_linear_group); other shapes run one product per launch
+ * and accumulate dX through the tensor type (rounded after each).  scratch:
  * gta_sga_layer_scratch_bytes.  Host-side sequencing of the entry points above.                  */
 size_t gta_sga_layer_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
 gta_status gta_sga_layer_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
