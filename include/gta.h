@@ -105,6 +105,15 @@ gta_status gta_plan_create(gta_plan** plan, const int64_t* indptr, const int32_t
                            void* workspace, size_t workspace_bytes, void* stream);
 void gta_plan_destroy(gta_plan* plan);
 
+/* Only the leading gta_plan_retained_bytes of the workspace stay in use once gta_plan_create has
+ * returned (the rest held sort buffers).  gta_plan_compact copies that part into new_workspace
+ * (device, 256-byte aligned, at least gta_plan_retained_bytes, not overlapping it) and makes the plan
+ * use the copy, after which the caller may release the original buffer: on the largest benchmark
+ * workload that leaves 0.9 GB instead of 1.9 GB beside the tensors.  Synchronises the stream; no
+ * other call may be using the plan meanwhile. */
+size_t gta_plan_retained_bytes(int64_t n_dst, int64_t n_src, int64_t nnz, const gta_plan_opts* opts);
+gta_status gta_plan_compact(gta_plan* plan, void* new_workspace, size_t new_workspace_bytes, void* stream);
+
 gta_status gta_plan_get_info(const gta_plan* plan, gta_plan_info* info /* host */);
 
 /* Copies plan arrays to HOST buffers (any may be NULL to skip); synchronises the device.

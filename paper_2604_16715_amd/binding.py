@@ -59,6 +59,10 @@ def load_library():
     lib.gta_plan_create.restype = c_int
     lib.gta_plan_create.argtypes = [POINTER(vp), vp, vp, c_int64, c_int64, c_int64, POINTER(_PlanOpts),
                                     vp, c_size_t, vp]
+    lib.gta_plan_retained_bytes.restype = c_size_t
+    lib.gta_plan_retained_bytes.argtypes = [c_int64, c_int64, c_int64, POINTER(_PlanOpts)]
+    lib.gta_plan_compact.restype = c_int
+    lib.gta_plan_compact.argtypes = [vp, vp, c_size_t, vp]
     lib.gta_plan_destroy.restype = None
     lib.gta_plan_destroy.argtypes = [vp]
     lib.gta_plan_get_info.restype = c_int
@@ -237,9 +241,10 @@ class Plan:
 
 
 def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pack_max_deg=0,
-                    wave_max_deg=0, hub_chunk=0, validate=True, keep_dz_min_nnz=0) -> Plan:
+                    wave_max_deg=0, hub_chunk=0, validate=True, keep_dz_min_nnz=0, compact=True) -> Plan:
     """The plan is built once per graph, so the CSR arrays are checked on the device by default
-    (validate=True): the kernels that use the plan do not bounds-check the indices."""
+    (validate=True): the kernels that use the plan do not bounds-check the indices.  compact=True
+    moves the plan into a buffer of just the size it keeps using and drops the build workspace."""
     lib = load_library()
     if not isinstance(indptr, torch.Tensor) or not isinstance(indices, torch.Tensor):
         raise GtaError(1, "indptr and indices must be tensors")
@@ -261,6 +266,14 @@ def gta_plan_create(indptr: torch.Tensor, indices: torch.Tensor, n_src: int, pac
     handle = c_void_p()
     _check(lib.gta_plan_create(ctypes.byref(handle), _ptr(indptr), _ptr(indices), n_dst, n_src, nnz,
                                ctypes.byref(opts), _ptr(workspace), nbytes, _stream()))
+    if compact:
+        keep = lib.gta_plan_retained_bytes(n_dst, n_src, nnz, ctypes.byref(opts))
+        small = torch.empty(max(keep, 256), dtype=torch.uint8, device=indptr.device)
+        status = lib.gta_plan_compact(handle, _ptr(small), small.numel(), _stream())
+        if status != 0:
+            lib.gta_plan_destroy(handle)
+            _check(status)
+        workspace = small
     return Plan(handle, workspace, indptr, indices, n_dst, n_src)
 
 

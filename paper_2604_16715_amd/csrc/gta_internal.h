@@ -36,6 +36,8 @@ struct gta_plan {
     int32_t pack_max_deg = 0, wave_max_deg = 0, hub_chunk = 0;
     int64_t keep_dz_min_nnz = 262144;
     int device = 0;
+    char* workspace = nullptr;     // device: base of the caller's buffer that holds every plan array
+    size_t retained_bytes = 0;     // its leading part that stays in use after the plan is built
     const int64_t* indptr = nullptr;
     const int32_t* indices = nullptr;
     int64_t* t_indptr = nullptr;   // device [n_src + 1]

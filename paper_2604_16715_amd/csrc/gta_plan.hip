@@ -5,6 +5,8 @@
 // their summation order.
 #include "gta_internal.h"
 
+#include <type_traits>
+
 #include <algorithm>
 #include <new>
 
@@ -276,7 +278,7 @@ bool resolve_opts(const gta_plan_opts* o, Opts* r) {
 
 struct Layout {
     size_t bin_rows[2], span[2], chunk_ptr[2], chunks[2], t_indptr, t_indices, t_eid, t_pos;
-    size_t key_a, key_b, val_a, val_b, hist, tile_sum, stats, flag, total;
+    size_t retained, key_a, key_b, val_a, val_b, hist, tile_sum, stats, flag, total;
     int64_t max_chunked[2], max_chunks[2], sort_cap, hist_cap, tile_cap;
 };
 
@@ -296,6 +298,7 @@ void make_layout(int64_t n_dst, int64_t n_src, int64_t nnz, const Opts& o, Layou
     L->t_indices = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, nnz));
     L->t_eid = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, nnz));
     L->t_pos = take(sizeof(int32_t) * (size_t)std::max<int64_t>(1, nnz));
+    L->retained = off;   // everything from here on is needed only while the plan is being built
     L->sort_cap = std::max<int64_t>(1, std::max(nnz, std::max(n_dst, n_src)));
     L->key_a = take(4 * (size_t)L->sort_cap);
     L->key_b = take(4 * (size_t)L->sort_cap);
@@ -467,6 +470,8 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
     p->pack_max_deg = o.pack; p->wave_max_deg = o.wave; p->hub_chunk = o.chunk;
     p->keep_dz_min_nnz = o.keep_dz;
     p->indptr = indptr; p->indices = indices;
+    p->workspace = b.ws;
+    p->retained_bytes = b.L.retained;
     GTA_HIP_TRY(hipGetDevice(&p->device));
 
     if (o.validate) {
@@ -522,6 +527,48 @@ extern "C" GTA_API gta_status gta_plan_create(gta_plan** out, const int64_t* ind
     GTA_HIP_TRY(hipStreamSynchronize(b.st));
     guard.p = nullptr;
     *out = p;
+    return GTA_OK;
+}
+
+extern "C" GTA_API size_t gta_plan_retained_bytes(int64_t n_dst, int64_t n_src, int64_t nnz, const gta_plan_opts* opts) {
+    Opts o;
+    if (n_dst < 0 || n_src < 0 || nnz < 0 || n_dst >= (1ll << 31) || n_src >= (1ll << 31) ||
+        nnz > kMaxNnz || !resolve_opts(opts, &o))
+        return 0;
+    Layout L;
+    make_layout(n_dst, n_src, nnz, o, &L);
+    return L.retained;
+}
+
+extern "C" GTA_API gta_status gta_plan_compact(gta_plan* p, void* new_workspace, size_t new_bytes, void* stream) {
+    if (!p || !new_workspace) return fail(GTA_ERR_INVALID_ARG, "null pointer argument");
+    if (((uintptr_t)new_workspace & 255) != 0) return fail(GTA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (new_bytes < p->retained_bytes)
+        return fail(GTA_ERR_WORKSPACE, "the new workspace has %zu bytes, %zu needed", new_bytes, p->retained_bytes);
+    int device = -1;
+    GTA_HIP_TRY(hipGetDevice(&device));
+    if (device != p->device)
+        return fail(GTA_ERR_INVALID_ARG, "the plan lives on device %d, the current device is %d", p->device, device);
+    char* to = static_cast<char*>(new_workspace);
+    if (to == p->workspace) return GTA_OK;
+    if (to < p->workspace + p->retained_bytes && p->workspace < to + p->retained_bytes)
+        return fail(GTA_ERR_INVALID_ARG, "the new workspace overlaps the retained part of the old one");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    GTA_HIP_TRY(hipMemcpyAsync(to, p->workspace, p->retained_bytes, hipMemcpyDeviceToDevice, st));
+    GTA_HIP_TRY(hipStreamSynchronize(st));
+    const ptrdiff_t shift = to - p->workspace;
+    auto move = [shift](auto*& ptr) {
+        typedef std::remove_reference_t<decltype(ptr)> P;
+        if (ptr) ptr = reinterpret_cast<P>(reinterpret_cast<char*>(const_cast<std::remove_const_t<std::remove_pointer_t<P>>*>(ptr)) + shift);
+    };
+    move(p->t_indptr); move(p->t_indices); move(p->t_eid); move(p->t_pos);
+    for (int s = 0; s < 2; ++s) {
+        Side& sd = p->side[s];
+        move(sd.bin_rows); move(sd.span); move(sd.chunk_ptr); move(sd.chunks);
+    }
+    p->side[1].ptr = p->t_indptr;   // the source side walks the transposed pattern (the destination side the caller's CSR)
+    p->side[1].idx = p->t_indices;
+    p->workspace = to;
     return GTA_OK;
 }
 

@@ -61,3 +61,49 @@ def test_plan_rejects_malformed_graph():
     with pytest.raises(gta.GtaError) as e:
         gta.gta_plan_create(indptr, indices, 1, validate=False)   # n_src < n_dst
     assert e.value.status == 1
+
+
+def test_plan_compaction_keeps_every_array_and_result():
+    """gta_plan_compact moves the plan into a buffer of the retained size: the exported arrays are those
+    of the plan built in place, and attention through the moved plan (with the build workspace
+    overwritten) gives the bits of the in-place one."""
+    import paper_2604_16715_amd as gta
+    from helpers import Problem, to_torch
+    w = gen.workload("mid", 4)
+    p = Problem.from_workload(w)
+    d_ptr, d_idx = torch.from_numpy(w.indptr).cuda(), torch.from_numpy(w.indices).cuda()
+    kw = dict(wave_max_deg=16, hub_chunk=64, keep_dz_min_nnz=1)
+    in_place = gta.gta_plan_create(d_ptr, d_idx, w.n_src, compact=False, **kw)
+    lib = gta.load_library()
+    import ctypes
+    opts = gta.binding._PlanOpts(0, kw["wave_max_deg"], kw["hub_chunk"], 1, kw["keep_dz_min_nnz"])
+    keep = lib.gta_plan_retained_bytes(w.n_dst, w.n_src, w.nnz, ctypes.byref(opts))
+    assert 0 < keep < in_place.workspace.numel()
+    moved = gta.gta_plan_create(d_ptr, d_idx, w.n_src, compact=True, **kw)
+    assert moved.workspace.numel() == max(keep, 256)
+    a, b = in_place.export_transpose(), moved.export_transpose()
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+    for side in (0, 1):
+        a, b = in_place.export_bins(side), moved.export_bins(side)
+        for k in ("bin_rows", "bin_off", "chunk_ptr", "chunks"):
+            np.testing.assert_array_equal(a[k], b[k], err_msg=f"side {side} {k}")
+    # compaction through the C ABI by hand, then the old buffer is filled with garbage
+    third = gta.gta_plan_create(d_ptr, d_idx, w.n_src, compact=False, **kw)
+    old = third.workspace
+    new = torch.empty(keep, dtype=torch.uint8, device="cuda")
+    rc = lib.gta_plan_compact(third.handle, new.data_ptr(), new.numel(), None)
+    assert rc == 0, lib.gta_last_error().decode()
+    old.fill_(0xA5)
+    third.workspace = new
+    assert lib.gta_plan_compact(third.handle, new.data_ptr() + 256, new.numel(), None) == 1   # overlapping target
+    Q, K, V, dO = (to_torch(getattr(p, k)) for k in ("Q", "K", "V", "dO"))
+    ref_out, ref_lse = gta.gta_attn_fwd(in_place, Q, K, V)
+    ref_grads = gta.gta_attn_bwd(in_place, Q, K, V, ref_out, ref_lse, dO)
+    for plan in (moved, third):
+        out, lse = gta.gta_attn_fwd(plan, Q, K, V)
+        grads = gta.gta_attn_bwd(plan, Q, K, V, out, lse, dO)
+        assert torch.equal(out, ref_out) and torch.equal(lse, ref_lse)
+        for g, r in zip(grads, ref_grads):
+            assert torch.equal(g, r)
+    torch.cuda.synchronize()
