@@ -43,7 +43,7 @@ def profile_counters(workload: str) -> dict:
     return table
 
 
-def survey_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int):
+def scope_table_bytes(pass_name: str, rows: int, entries: int, row_bytes: int, heads: int):
     """Algorithmic bytes of a pass by the scope table's per-unit figures (every entry gathers its rows,
     streams touched once, nothing kept per entry), or None for kernels that table has no row for:
       forward                      E (2R + 4)      + N_dst (2R + 4H + 8)
@@ -391,8 +391,8 @@ def main() -> int:
     traffic, l2_hit, craw = counter_fields(dom_name)
     # the dominant kernel by the scope table's formula (when it has a row for it) and by the bytes this
     # implementation moves (`lean` form: the two coincide; default form: + the dZ store and its index)
-    dom_survey = survey_bytes(dom_name, dom["rows"], dom["entries"], row_bytes, w.heads)
-    dom_survey = dom["bytes"] if dom_survey is None else dom_survey
+    dom_scope = scope_table_bytes(dom_name, dom["rows"], dom["entries"], row_bytes, w.heads)
+    dom_scope = dom["bytes"] if dom_scope is None else dom_scope
     gbs = lambda nbytes: nbytes / (dom["avg_ms"] * 1e-3) / 1e9
     step_gbs = total_bytes / (ms_per_step * 1e-3) / 1e9
     result = {
@@ -417,12 +417,12 @@ def main() -> int:
                         "this can exceed what a streaming kernel reaches (the *_ceiling_gbs probes, "
                         "measured in this run)"},
         "kernels": {n: {"avg_ms": round(k["avg_ms"], 4), "gbs": round(k["gbs"], 1)} for n, k in kernels.items()},
-        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": gbs(dom_survey), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": gbs(dom_survey) / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": dom_survey, "avg_launch_ms": dom["avg_ms"],
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": gbs(dom_scope), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbs(dom_scope) / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": dom_scope, "avg_launch_ms": dom["avg_ms"],
                      "achieved_impl_model": gbs(dom["bytes"]), "frac_impl_model": gbs(dom["bytes"]) / HBM_PEAK_GBS,
                      "bytes_per_launch_impl_model": dom["bytes"],
-                     "frac_of_read_ceiling": gbs(dom_survey) / ceilings["read"] if ceilings else None,
+                     "frac_of_read_ceiling": gbs(dom_scope) / ceilings["read"] if ceilings else None,
                      "l2_hit_pct": l2_hit,
                      "traffic_note": None if craw is None else
                      f"L2<->fabric bytes per launch (Infinity-Cache hits included; no gfx950 counter separates "
