@@ -327,7 +327,8 @@ int gta_profile_read(gta_launch_record* out, int cap, int reset);
 
 /* Streaming probe for benchmarks: one plain kernel over `bytes` bytes (a multiple of 16) per operand,
  * so that the attention passes can be read against the bandwidth a streaming kernel reaches on the
- * same GPU in the same run.  mode 0: reads a (dst needs 16 valid bytes and is left unchanged);
+ * same GPU in the same run.  mode 0: reads a (dst needs 16 writable bytes; they are written only if the
+ * XOR of everything a thread read equals one chosen 32-bit pattern, which is what keeps the reads alive);
  * mode 1: dst = a; mode 2: dst = a + b as floats.  Timed like every other launch while
  * gta_profile_enable is on (records "probe_read" / "probe_copy" / "probe_add", entries = bytes / 16). */
 gta_status gta_stream_probe(int mode, void* dst, const void* a, const void* b, size_t bytes, void* stream);

@@ -15,7 +15,6 @@ namespace {
 
 constexpr int kSortThreads = 256;                 // 4 wavefronts
 constexpr int kWaveItems = 2048;                  // keys one wavefront ranks, in order
-constexpr int kBlockItems = kWaveItems * (kSortThreads / 64);
 constexpr int kScanTile = 2048;                   // 256 threads x 8
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }

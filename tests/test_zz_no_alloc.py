@@ -90,3 +90,36 @@ def test_bf16_and_size_limit():
         gta.gta_attn_fwd_noalloc(plan, Q, Q, Q, out, lse)
     assert err.value.status == 3 and "built-in scratch" in str(err.value)
     torch.cuda.synchronize()
+
+
+def test_under_graph_capture():
+    """What the entry point is for: a caller under HIP graph capture, which cannot allocate.  The
+    address look-up happens on the eager call before the capture; replays are checked against the
+    eager result with eager work and synchronisations in between."""
+    import paper_2604_16715_amd as gta
+    p = Problem.from_workload(gen.workload("mid", 8))
+    plan = gta.gta_plan_create(torch.from_numpy(p.indptr).cuda(), torch.from_numpy(p.indices).cuda(), p.n_src,
+                               wave_max_deg=16, hub_chunk=64)
+    assert plan.info().n_hub[0] > 0
+    Q, K, V = (to_torch(getattr(p, k)) for k in ("Q", "K", "V"))
+    out, lse = torch.empty_like(Q), torch.empty((p.n_dst, Q.shape[1]), dtype=torch.float32, device="cuda")
+    print(f"noalloc: graph capture, nnz={int(p.indptr[-1])}", flush=True)
+    gta.gta_attn_fwd_noalloc(plan, Q, K, V, out, lse)
+    torch.cuda.synchronize()
+    ref = (out.clone(), lse.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            gta.gta_attn_fwd_noalloc(plan, Q, K, V, out, lse)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref[0]) and torch.equal(lse, ref[1]), f"replay {rep} differs from the eager result"
+        gta.gta_attn_fwd_noalloc(plan, Q, K, V, out, lse)   # eager work between replays
+        torch.cuda.synchronize()
