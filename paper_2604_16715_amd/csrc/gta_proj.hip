@@ -34,7 +34,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kProjThreads = 512, kProjRows = 128, kProjKC = 32, kProjWPitch = kProjKC + 8;
+constexpr int kProjConsumers = 8;                      // multiplying wavefronts of a workgroup
+constexpr int kProjThreads = 64 * (kProjConsumers + 4);   // + 2 weight fetchers + 2 X tile fetchers
+constexpr int kProjRows = 128, kProjKC = 32, kProjWPitch = kProjKC + 8;
 constexpr int kProjMaxParts = 4;
 
 __device__ __forceinline__ bf16x8 frag_of(const u32x4& u) { return __builtin_bit_cast(bf16x8, u); }
@@ -87,237 +89,304 @@ template <int D> struct ProjShape {
         sizeof(uint16_t) * ((size_t)kProjRows * XPitch + 2 * (size_t)D * kProjWPitch + 8 * 32 * (size_t)PPitch);
 };
 
-template <int D, int P_IN, int P_OUT, bool HAS_C>
-__global__ void __launch_bounds__(kProjThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-k_proj(ProjArgs a) {
-    using S = ProjShape<D>;
-    constexpr int CT = S::CT, RT = S::RT, XPitch = S::XPitch, PPitch = S::PPitch, KCH = S::KCH;
-    constexpr int WPitch = kProjWPitch;
-    // Global loads are split by wavefront: wavefronts 0-3 fetch the weight chunks, wavefronts 4-7 the X tiles
-    // (and every wavefront multiplies).  A wavefront's loads complete in order, so a wavefront that had an
-    // X tile (HBM latency) in flight would have to sit it out at its next wait for a weight chunk (L2 latency).
-    constexpr int kLoaders = kProjThreads / 2;
-    constexpr int XUnitsPerRow = D / 8, XU = kProjRows * XUnitsPerRow / kLoaders;   // X tile units per loading thread
-    constexpr int WUnits = D * (kProjKC / 8);                                      // units of a weight chunk
-    constexpr int WU = WUnits / kLoaders;
-    static_assert(WUnits % kLoaders == 0 && (kProjRows * XUnitsPerRow) % kLoaders == 0, "whole units per loader");
-    constexpr int UPR = 4 * CT, RPI = 64 / UPR, NI = 32 / RPI;   // result patch: units per row, rows per instruction
+// The walk over (row block, output, input, weight chunk) that every wavefront of a workgroup makes, with
+// the workgroup barriers in it; what a wavefront does between the barriers depends on its role (hooks).
+template <int P_IN, int P_OUT, int KCH, class Hooks>
+__device__ __forceinline__ void proj_walk(int64_t row_blocks, Hooks& h) {
     constexpr int TOTAL_CHUNKS = P_OUT * P_IN * KCH;
-    extern __shared__ __align__(16) unsigned char proj_lds[];
-    uint16_t* xs = reinterpret_cast<uint16_t*>(proj_lds);        // [128][XPitch]
-    uint16_t* ws = xs + kProjRows * XPitch;                      // [2][D][WPitch]
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 5, r32 = lane & 31;
-    const int wr = w / S::WAVES_C, wc = w % S::WAVES_C;
-    const bool loads_w = w < 4;                     // wave-uniform role
-    const unsigned lt = (unsigned)tid & (kLoaders - 1);   // index among the threads of the same role
-    uint16_t* patch = ws + 2 * D * WPitch + w * (32 * PPitch);   // this wavefront's [32][PPitch]
-    const int crow = lane / UPR, cunit = lane % UPR;             // this lane's unit of a patch row group
-    const int col0 = wc * CT * 32;                               // first column of this wavefront
-
-    u32x4 xregs[XU], wregs[2][WU], cregs[HAS_C ? RT * NI : 1];
-    // Global addresses are a per-block base (uniform, kept in scalar registers) plus a 32-bit element
-    // offset inside the block's 128 x D window; rows past the end of the tensor are clamped to its last
-    // row.  (64-bit per-thread addresses for every load would not fit the register budget.)
-    auto rows_in_block = [&](int64_t rb) {   // valid rows of block rb, at least 1
-        const int64_t left = a.n - rb * kProjRows;
-        return (int)(left < kProjRows ? left : kProjRows);
-    };
-    auto load_x = [&](int64_t rb, int pi) {   // X_pi rows of block rb -> registers
-        if (loads_w) return;
-        const char* base = reinterpret_cast<const char*>(a.X[pi] + rb * (kProjRows * D));
-        const unsigned lim = (unsigned)rows_in_block(rb) - 1u;
-#pragma unroll
-        for (int i = 0; i < XU; ++i) {
-            const unsigned u = lt + i * kLoaders, r = u / XUnitsPerRow, cu = u % XUnitsPerRow;
-            const unsigned off = ((r < lim ? r : lim) * D + cu * 8) * 2u;   // bytes
-            xregs[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
-        }
-    };
-    auto store_x = [&]() {
-        if (loads_w) return;
-#pragma unroll
-        for (int i = 0; i < XU; ++i) {
-            const unsigned u = lt + i * kLoaders, r = u / XUnitsPerRow, cu = u % XUnitsPerRow;
-            *reinterpret_cast<u32x4*>(xs + r * XPitch + cu * 8) = xregs[i];
-        }
-    };
-    auto load_w = [&](int set, int ci) {      // packed chunk ci -> register set `set`
-        if (!loads_w) return;
-        const char* src = reinterpret_cast<const char*>(a.Wp + (int64_t)ci * (D * kProjKC));
-#pragma unroll
-        for (int i = 0; i < WU; ++i) {
-            const unsigned u = lt + i * kLoaders;
-            wregs[set][i] = *reinterpret_cast<const u32x4*>(src + u * 16u);
-        }
-    };
-    auto store_w = [&](int set, int buf) {
-        if (!loads_w) return;
-        uint16_t* dst = ws + buf * (D * WPitch);
-#pragma unroll
-        for (int i = 0; i < WU; ++i) {
-            const unsigned u = lt + i * kLoaders;
-            *reinterpret_cast<u32x4*>(dst + (u >> 2) * WPitch + (u & 3) * 8) = wregs[set][i];
-        }
-    };
-    auto wrap = [](int ci) { return ci >= TOTAL_CHUNKS ? ci - TOTAL_CHUNKS : ci; };
-    auto load_c = [&](int64_t rb, int po) {   // this wavefront's tile of the addend, in patch-row order
-        if constexpr (HAS_C) {
-            const char* base = reinterpret_cast<const char*>(a.C[po] + rb * (kProjRows * D));
-            const unsigned lim = (unsigned)rows_in_block(rb) - 1u;
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                for (int q = 0; q < NI; ++q) {
-                    const unsigned r = (unsigned)((wr * RT + rt) * 32 + RPI * q + crow);
-                    const unsigned off = ((r < lim ? r : lim) * D + (unsigned)(col0 + 8 * cunit)) * 2u;
-                    cregs[rt * NI + q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
-                }
-        }
-    };
-
-    floatx16 acc[RT][CT];
-    auto zero_acc = [&]() {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[rt][ct][v] = 0.f;
-    };
-    auto compute = [&](int kc, int buf) {     // one weight chunk: two k steps of 16
-        const uint16_t* wb = ws + buf * (D * WPitch) + (col0 + r32) * WPitch + 8 * g;
-        const uint16_t* xb = xs + (wr * RT * 32 + r32) * XPitch + kc * kProjKC + 8 * g;
-        constexpr int KS = kProjKC / 16;
-        u32x4 xf[KS][RT], wf[KS][CT];
-        // all fragment reads of the chunk first, then the matrix instructions: the reads' latency is paid once
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) xf[ks][rt] = *reinterpret_cast<const u32x4*>(xb + rt * 32 * XPitch + 16 * ks);
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) wf[ks][ct] = *reinterpret_cast<const u32x4*>(wb + ct * 32 * WPitch + 16 * ks);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(wf[ks][ct]), frag_of(xf[ks][rt]),
-                                                                          acc[rt][ct], 0, 0, 0);
-    };
-    // rounds the wavefront's tiles (after adding the addend), lays each 32-row group out row-major in
-    // the patch and stores it in whole 16-byte units; rows past the end are not stored
-    auto epilogue = [&](int64_t rb, int po) {
-        char* ybase = reinterpret_cast<char*>(a.Y[po] + rb * (kProjRows * D));
-        const int valid = rows_in_block(rb);
-        uint16_t* mine = patch + r32 * PPitch + 4 * g;   // this lane's 8-byte pieces: + 32 ct + 8 (v / 4)
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            if constexpr (HAS_C) {
-                wave_fence();
-#pragma unroll
-                for (int q = 0; q < NI; ++q)
-                    *reinterpret_cast<u32x4*>(patch + (RPI * q + crow) * PPitch + 8 * cunit) = cregs[rt * NI + q];
-                wave_fence();
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                    for (int qd = 0; qd < 4; ++qd) {
-                        const u32x2 c = *reinterpret_cast<const u32x2*>(mine + 32 * ct + 8 * qd);
-                        acc[rt][ct][4 * qd + 0] += __uint_as_float(c.x << 16);
-                        acc[rt][ct][4 * qd + 1] += __uint_as_float(c.x & 0xFFFF0000u);
-                        acc[rt][ct][4 * qd + 2] += __uint_as_float(c.y << 16);
-                        acc[rt][ct][4 * qd + 3] += __uint_as_float(c.y & 0xFFFF0000u);
-                    }
-            }
-            wave_fence();
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    u32x2 o;
-                    o.x = pack2(acc[rt][ct][4 * qd + 0], acc[rt][ct][4 * qd + 1]);
-                    o.y = pack2(acc[rt][ct][4 * qd + 2], acc[rt][ct][4 * qd + 3]);
-                    *reinterpret_cast<u32x2*>(mine + 32 * ct + 8 * qd) = o;
-                }
-            wave_fence();
-#pragma unroll
-            for (int q = 0; q < NI; ++q) {
-                const int r = (wr * RT + rt) * 32 + RPI * q + crow;
-                if (r < valid)
-                    __builtin_nontemporal_store(
-                        *reinterpret_cast<const u32x4*>(patch + (RPI * q + crow) * PPitch + 8 * cunit),
-                        reinterpret_cast<u32x4*>(ybase + (unsigned)(r * D + col0 + 8 * cunit) * 2u));
-            }
-        }
-    };
-
+    static_assert(KCH % 2 == 0, "chunks per product");   // chunk parity = LDS buffer, kept static by the pair below
+    auto wrap = [](int ci) { return ci % TOTAL_CHUNKS; };   // (TOTAL_CHUNKS can be as small as 2)
     int64_t rb = blockIdx.x;
-    if (rb >= a.row_blocks) return;   // whole workgroup leaves together
-    // The weight chunks run two ahead: while chunk c is multiplied out of LDS buffer c % 2, chunk c + 1
-    // sits in a register set (fetched during chunk c - 1, stored to the other buffer after the
-    // multiplication) and chunk c + 2 is being fetched into the other set, so an L2 round trip has
-    // two chunks' worth of matrix work to hide behind.  Chunk parity = buffer = register set, which
-    // the loop unrolled by two keeps static (every product has an even number of chunks).
-    static_assert(KCH % 2 == 0, "chunks per product");
-    load_x(rb, 0);
-    load_w(0, 0);
-    store_x();
-    store_w(0, 0);
-    load_w(1, wrap(1));
+    if (rb >= row_blocks) return;   // whole workgroup leaves together
+    h.prologue(rb);
     __syncthreads();
-    int ci = 0;   // chunk being multiplied (always even at the top of the unrolled pair)
-    for (; rb < a.row_blocks; rb += gridDim.x) {
+    int ci = 0;   // chunk being multiplied (even at the top of the pair)
+    for (; rb < row_blocks; rb += gridDim.x) {
         // the block after this one (when there is none: this one again, fetched and never used)
-        const int64_t next_rb = rb + gridDim.x < a.row_blocks ? rb + gridDim.x : rb;
+        const int64_t next_rb = rb + gridDim.x < row_blocks ? rb + gridDim.x : rb;
 #pragma unroll
         for (int po = 0; po < P_OUT; ++po) {
-            zero_acc();
+            h.begin_output();
 #pragma unroll
             for (int pi = 0; pi < P_IN; ++pi) {
                 const bool last_of_block = po == P_OUT - 1 && pi == P_IN - 1;
                 // the X tile changes after this product unless the next product reads the same input
-                constexpr bool shared_x = P_IN == 1;
-                const bool swap_x = !shared_x || po == P_OUT - 1;
-                if (swap_x) load_x(last_of_block ? next_rb : rb, (pi + 1) % P_IN);
-                if (pi == P_IN - 1) load_c(rb, po);
+                const bool swap_x = P_IN > 1 || po == P_OUT - 1;
+                h.begin_product(rb, last_of_block ? next_rb : rb, po, pi, (pi + 1) % P_IN, swap_x);
 #pragma unroll 1
                 for (int kc = 0; kc < KCH; kc += 2) {
-                    load_w(0, wrap(ci + 2));
-                    __builtin_amdgcn_sched_barrier(0);   // the fetch is issued before the multiplication, not after
-                    compute(kc, 0);
-                    store_w(1, 1);      // buffer 1 was last read during the previous chunk, before its barrier
+                    h.chunk(kc, 0, wrap(ci + 3));
                     __syncthreads();
-                    load_w(1, wrap(ci + 3));
-                    __builtin_amdgcn_sched_barrier(0);
-                    compute(kc + 1, 1);
-                    store_w(0, 0);
+                    h.chunk(kc + 1, 1, wrap(ci + 4));
                     __syncthreads();
                     ci = wrap(ci + 2);
                 }
-                if (swap_x) store_x();  // every wavefront has passed the last chunk's barrier: the tile is free
-                if (pi == P_IN - 1) epilogue(rb, po);
+                h.end_product(rb, po, pi, swap_x);   // every wavefront has passed the last chunk's barrier: the X tile is free
                 if (swap_x) __syncthreads();
             }
         }
     }
 }
 
-template <int D, int P_IN, int P_OUT, bool HAS_C>
-gta_status launch_proj(const ProjArgs& a, hipStream_t st) {
+// 12 wavefronts: 8 multiply (two per SIMD), 2 fetch the weight chunks, 2 fetch the X tiles (one fetcher per
+// SIMD).  The multiplying wavefronts issue nothing but fragment reads and matrix instructions between two
+// barriers; a fetching wavefront's waits for memory stall nobody else.  Weight and tile fetches are in
+// different wavefronts because a wavefront's loads complete in order: behind a tile (HBM latency) every later
+// weight chunk (L2 latency) would wait as well.
+//
+// Row blocks: block rb covers rows [row0, row0 + 128) with row0 = min(128 rb, n - 128), i.e. the last block
+// of a tensor whose row count is not a multiple of 128 is moved back so that it is whole (it recomputes
+// and rewrites some rows of the block before it with the same bits).  No load or store in the main form
+// needs a bounds check that way, which keeps every address "scalar base + one offset register".  Tensors
+// of fewer than 128 rows take the SMALL form: one block, rows past the end clamped / not stored.
+template <int D, int P_IN, int P_OUT, bool HAS_C, bool SMALL>
+__global__ void __launch_bounds__(kProjThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+k_proj(ProjArgs a) {
+    using S = ProjShape<D>;
+    constexpr int CT = S::CT, RT = S::RT, XPitch = S::XPitch, PPitch = S::PPitch, KCH = S::KCH;
+    constexpr int WPitch = kProjWPitch;
+    constexpr int kFetchers = 128;                               // threads of each fetching role
+    constexpr int XUnitsPerRow = D / 8, XU = kProjRows * XUnitsPerRow / kFetchers;   // X tile units per fetching thread
+    constexpr int WUnits = D * (kProjKC / 8);                    // 16-byte units of a weight chunk
+    constexpr int WU = WUnits / kFetchers;
+    static_assert(WUnits % kFetchers == 0 && (kProjRows * XUnitsPerRow) % kFetchers == 0, "whole units per fetcher");
+    constexpr int UPR = 4 * CT, RPI = 64 / UPR, NI = 32 / RPI;   // result patch: units per row, rows per instruction
+    extern __shared__ __align__(16) unsigned char proj_lds[];
+    uint16_t* xs = reinterpret_cast<uint16_t*>(proj_lds);        // [128][XPitch]
+    uint16_t* ws = xs + kProjRows * XPitch;                      // [2][D][WPitch]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront index, in a scalar register
+    // Global addresses are a per-block base (uniform, kept in scalar registers) plus an unsigned 32-bit byte
+    // offset inside the block's 128 x D window.
+
+    if (w < kProjConsumers) {
+        // ---------------------------------------------------------------- multiplying wavefronts
+        const int g = lane >> 5, r32 = lane & 31;
+        const int wr = w / S::WAVES_C, wc = w % S::WAVES_C;
+        uint16_t* patch = ws + 2 * D * WPitch + w * (32 * PPitch);   // this wavefront's [32][PPitch]
+        const int crow = lane / UPR, cunit = lane % UPR;             // this lane's unit of a patch row group
+        const int col0 = wc * CT * 32;                               // first column of this wavefront
+        struct Consumer {
+            const ProjArgs& a;
+            uint16_t *xs, *ws, *patch;
+            int g, r32, wr, crow, cunit, col0;
+            floatx16 acc[RT][CT];
+            u32x4 cregs[HAS_C ? RT * NI : 1];
+            __device__ __forceinline__ int64_t row0(int64_t rb) const {   // first row of block rb
+                if (SMALL) return 0;
+                const int64_t r = rb * kProjRows, last = a.n - kProjRows;
+                return r < last ? r : last;
+            }
+            __device__ __forceinline__ void prologue(int64_t) {}
+            __device__ __forceinline__ void begin_output() {
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[rt][ct][v] = 0.f;
+            }
+            // the addend's tile of this wavefront, in patch-row order, fetched a whole product ahead of its use
+            __device__ __forceinline__ void begin_product(int64_t rb, int64_t, int po, int pi, int, bool) {
+                if constexpr (HAS_C) {
+                    if (pi != P_IN - 1) return;
+                    const char* base = reinterpret_cast<const char*>(a.C[po] + row0(rb) * D);
+                    const unsigned lim = SMALL ? (unsigned)a.n - 1u : kProjRows - 1u;
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                        for (int q = 0; q < NI; ++q) {
+                            unsigned r = (unsigned)((wr * RT + rt) * 32 + RPI * q + crow);
+                            if (SMALL) r = r < lim ? r : lim;
+                            const unsigned off = (r * D + (unsigned)(col0 + 8 * cunit)) * 2u;
+                            cregs[rt * NI + q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
+                        }
+                }
+            }
+            __device__ __forceinline__ void chunk(int kc, int buf, int) {   // one weight chunk: two k steps of 16
+                const uint16_t* wb = ws + buf * (D * WPitch) + (col0 + r32) * WPitch + 8 * g;
+                const uint16_t* xb = xs + (wr * RT * 32 + r32) * XPitch + kc * kProjKC + 8 * g;
+                constexpr int KS = kProjKC / 16;
+                u32x4 xf[KS][RT], wf[KS][CT];
+                // all fragment reads of the chunk first, then the matrix instructions: the reads' latency is paid once
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) xf[ks][rt] = *reinterpret_cast<const u32x4*>(xb + rt * 32 * XPitch + 16 * ks);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) wf[ks][ct] = *reinterpret_cast<const u32x4*>(wb + ct * 32 * WPitch + 16 * ks);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct)
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(wf[ks][ct]), frag_of(xf[ks][rt]),
+                                                                                  acc[rt][ct], 0, 0, 0);
+            }
+            // rounds the wavefront's tiles (after adding the addend), lays each 32-row group out row-major in
+            // the patch and stores it in whole 16-byte units; rows past the end are not stored
+            __device__ __forceinline__ void end_product(int64_t rb, int po, int pi, bool) {
+                if (pi != P_IN - 1) return;
+                char* ybase = reinterpret_cast<char*>(a.Y[po] + row0(rb) * D);
+                const int valid = SMALL ? (int)a.n : kProjRows;
+                uint16_t* mine = patch + r32 * PPitch + 4 * g;   // this lane's 8-byte pieces: + 32 ct + 8 (v / 4)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    if constexpr (HAS_C) {
+                        wave_fence();
+#pragma unroll
+                        for (int q = 0; q < NI; ++q)
+                            *reinterpret_cast<u32x4*>(patch + (RPI * q + crow) * PPitch + 8 * cunit) = cregs[rt * NI + q];
+                        wave_fence();
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                            for (int qd = 0; qd < 4; ++qd) {
+                                const u32x2 c = *reinterpret_cast<const u32x2*>(mine + 32 * ct + 8 * qd);
+                                acc[rt][ct][4 * qd + 0] += __uint_as_float(c.x << 16);
+                                acc[rt][ct][4 * qd + 1] += __uint_as_float(c.x & 0xFFFF0000u);
+                                acc[rt][ct][4 * qd + 2] += __uint_as_float(c.y << 16);
+                                acc[rt][ct][4 * qd + 3] += __uint_as_float(c.y & 0xFFFF0000u);
+                            }
+                    }
+                    wave_fence();
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd) {
+                            u32x2 o;
+                            o.x = pack2(acc[rt][ct][4 * qd + 0], acc[rt][ct][4 * qd + 1]);
+                            o.y = pack2(acc[rt][ct][4 * qd + 2], acc[rt][ct][4 * qd + 3]);
+                            *reinterpret_cast<u32x2*>(mine + 32 * ct + 8 * qd) = o;
+                        }
+                    wave_fence();
+#pragma unroll
+                    for (int q = 0; q < NI; ++q) {
+                        const int r = (wr * RT + rt) * 32 + RPI * q + crow;
+                        if (!SMALL || r < valid)
+                            __builtin_nontemporal_store(
+                                *reinterpret_cast<const u32x4*>(patch + (RPI * q + crow) * PPitch + 8 * cunit),
+                                reinterpret_cast<u32x4*>(ybase + (unsigned)(r * D + col0 + 8 * cunit) * 2u));
+                    }
+                }
+            }
+        } h{a, xs, ws, patch, g, r32, wr, crow, cunit, col0, {}, {}};
+        proj_walk<P_IN, P_OUT, KCH>(a.row_blocks, h);
+    } else if (w < kProjConsumers + 2) {
+        // ---------------------------------------------------------------- weight fetchers
+        // While chunk c is multiplied out of LDS buffer c % 2: chunk c + 1 (fetched two chunks ago) goes from its
+        // register set into the other buffer, which was last read before the previous barrier, and chunk c + 3 is
+        // fetched into the set that just became free, so an L2 round trip has two chunks to complete in.
+        struct WeightFetcher {
+            const ProjArgs& a;
+            uint16_t* ws;
+            unsigned lt;
+            u32x4 regs[2][WU];
+            __device__ __forceinline__ void load(int set, int ci) {
+                const char* src = reinterpret_cast<const char*>(a.Wp + (int64_t)ci * (D * kProjKC));
+#pragma unroll
+                for (int i = 0; i < WU; ++i) regs[set][i] = *reinterpret_cast<const u32x4*>(src + (lt + i * kFetchers) * 16u);
+            }
+            __device__ __forceinline__ void store(int set, int buf) {
+                uint16_t* dst = ws + buf * (D * WPitch);
+#pragma unroll
+                for (int i = 0; i < WU; ++i) {
+                    const unsigned u = lt + i * kFetchers;
+                    *reinterpret_cast<u32x4*>(dst + (u >> 2) * WPitch + (u & 3) * 8) = regs[set][i];
+                }
+            }
+            __device__ __forceinline__ void prologue(int64_t) {
+                constexpr int TOTAL = P_OUT * P_IN * KCH;
+                load(0, 0);
+                store(0, 0);
+                load(1, 1 % TOTAL);
+                load(0, 2 % TOTAL);
+            }
+            __device__ __forceinline__ void begin_output() {}
+            __device__ __forceinline__ void begin_product(int64_t, int64_t, int, int, int, bool) {}
+            __device__ __forceinline__ void chunk(int, int buf, int fetch_ci) {
+                store(buf ^ 1, buf ^ 1);
+                load(buf ^ 1, fetch_ci);
+            }
+            __device__ __forceinline__ void end_product(int64_t, int, int, bool) {}
+        } h{a, ws, (unsigned)tid - 64u * kProjConsumers, {}};
+        proj_walk<P_IN, P_OUT, KCH>(a.row_blocks, h);
+    } else {
+        // ---------------------------------------------------------------- X tile fetchers (one tile ahead)
+        struct TileFetcher {
+            const ProjArgs& a;
+            uint16_t* xs;
+            unsigned lt;
+            u32x4 regs[XU];
+            // thread lt fetches the units (row r0 + i RSTEP, column unit cu): one offset register serves them all,
+            // the row step goes into the scalar base
+            __device__ __forceinline__ void load(int64_t rb, int pi) {
+                constexpr unsigned RSTEP = kFetchers / XUnitsPerRow;
+                static_assert(kFetchers % XUnitsPerRow == 0, "a fetching thread stays in one column unit");
+                int64_t first = 0;
+                if (!SMALL) {
+                    const int64_t r = rb * kProjRows, last = a.n - kProjRows;
+                    first = r < last ? r : last;
+                }
+                const char* base = reinterpret_cast<const char*>(a.X[pi] + first * D);
+                const unsigned r0 = lt / XUnitsPerRow, cu = lt % XUnitsPerRow;
+                if (!SMALL) {
+                    const unsigned off = (r0 * D + cu * 8) * 2u;
+#pragma unroll
+                    for (int i = 0; i < XU; ++i)
+                        regs[i] = __builtin_nontemporal_load(
+                            reinterpret_cast<const u32x4*>(base + (size_t)i * (RSTEP * D * 2) + off));
+                } else {                         // fewer than 128 rows: rows past the end read the last row
+                    const unsigned lim = (unsigned)a.n - 1u;
+#pragma unroll
+                    for (int i = 0; i < XU; ++i) {
+                        const unsigned r = r0 + i * RSTEP;
+                        regs[i] = __builtin_nontemporal_load(
+                            reinterpret_cast<const u32x4*>(base + ((r < lim ? r : lim) * D + cu * 8) * 2u));
+                    }
+                }
+            }
+            __device__ __forceinline__ void store() {
+                constexpr unsigned RSTEP = kFetchers / XUnitsPerRow;
+                uint16_t* dst = xs + (lt / XUnitsPerRow) * XPitch + (lt % XUnitsPerRow) * 8;
+#pragma unroll
+                for (int i = 0; i < XU; ++i) *reinterpret_cast<u32x4*>(dst + i * (RSTEP * XPitch)) = regs[i];
+            }
+            __device__ __forceinline__ void prologue(int64_t rb) { load(rb, 0); store(); }
+            __device__ __forceinline__ void begin_output() {}
+            __device__ __forceinline__ void begin_product(int64_t, int64_t next_tile_rb, int, int, int next_pi, bool swap_x) {
+                if (swap_x) load(next_tile_rb, next_pi);
+            }
+            __device__ __forceinline__ void chunk(int, int, int) {}
+            __device__ __forceinline__ void end_product(int64_t, int, int, bool swap_x) {
+                if (swap_x) store();
+            }
+        } h{a, xs, (unsigned)tid - 64u * (kProjConsumers + 2), {}};
+        proj_walk<P_IN, P_OUT, KCH>(a.row_blocks, h);
+    }
+}
+
+template <int D, int P_IN, int P_OUT, bool HAS_C, bool SMALL>
+gta_status launch_proj_form(const ProjArgs& a, hipStream_t st) {
     constexpr size_t lds = ProjShape<D>::lds_bytes;
-    GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_proj<D, P_IN, P_OUT, HAS_C>,
+    GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_proj<D, P_IN, P_OUT, HAS_C, SMALL>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     int device = 0, cus = 0;
     GTA_HIP_TRY(hipGetDevice(&device));
     GTA_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device));
     if (cus <= 0) cus = 256;
     const int64_t blocks = a.row_blocks < cus ? a.row_blocks : cus;
-    hipLaunchKernelGGL((k_proj<D, P_IN, P_OUT, HAS_C>), dim3((unsigned)blocks), dim3(kProjThreads), lds, st, a);
+    hipLaunchKernelGGL((k_proj<D, P_IN, P_OUT, HAS_C, SMALL>), dim3((unsigned)blocks), dim3(kProjThreads), lds, st, a);
     GTA_HIP_TRY(hipGetLastError());
     return GTA_OK;
+}
+template <int D, int P_IN, int P_OUT, bool HAS_C>
+gta_status launch_proj(const ProjArgs& a, hipStream_t st) {
+    return a.n < kProjRows ? launch_proj_form<D, P_IN, P_OUT, HAS_C, true>(a, st)
+                           : launch_proj_form<D, P_IN, P_OUT, HAS_C, false>(a, st);
 }
 
 template <int D> gta_status launch_proj_d(int p_in, int p_out, bool has_c, const ProjArgs& a, hipStream_t st) {
