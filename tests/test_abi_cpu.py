@@ -73,3 +73,25 @@ def test_null_arguments_are_rejected_before_any_gpu_call(lib):
     rc = lib.gta_attn_bwd_halo(None, None, None, None, None, None, None, None, 4, None, None, None, None, None,
                                None, None, None, 0, 4, 4, 16, 0, 0.0, None, 0, None)
     assert rc == 1 and b"plan" in lib.gta_last_error()
+
+
+def test_newer_entry_points_reject_bad_arguments_on_the_host(lib):
+    import ctypes
+    # the forward without scratch argument: same plan checks as gta_attn_fwd, before anything else
+    rc = lib.gta_attn_fwd_noalloc(None, None, None, None, None, None, None, None, 0, 0, 4, 16, 0, 0.0, None)
+    assert rc == 1 and b"plan" in lib.gta_last_error()
+    assert lib.gta_plan_compact(None, None, 0, None) == 1
+    assert lib.gta_plan_retained_bytes(-1, 1, 1, None) == 0
+    keep, whole = lib.gta_plan_retained_bytes(1000, 1500, 20000, None), lib.gta_plan_workspace_bytes(1000, 1500, 20000, None)
+    assert 20000 * 12 <= keep < whole          # three int32 arrays per entry stay, the sort buffers do not
+    # grouped projections: sizes, grouping and dtype are checked before any pointer is touched
+    assert lib.gta_linear_group_scratch_bytes(256, 1, 3) >= 3 * 256 * 256 * 2
+    assert lib.gta_linear_group_scratch_bytes(256, 5, 1) == 0
+    rc = lib.gta_linear_group(None, 1, None, 1, None, None, 10, 256, 0, 0, None, 0, None)      # fp32
+    assert rc == 2 and b"bfloat16" in lib.gta_last_error()
+    rc = lib.gta_linear_group(None, 1, None, 1, None, None, 10, 96, 1, 0, None, 0, None)       # d = 96
+    assert rc == 2
+    rc = lib.gta_linear_group(None, 1, None, 1, None, None, 10, 256, 1, 0, None, 0, None)      # null arrays
+    assert rc == 1
+    rc = lib.gta_stream_probe(3, None, None, None, 0, None)
+    assert rc == 1 and b"mode" in lib.gta_last_error()
