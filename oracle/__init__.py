@@ -34,18 +34,23 @@ def build(force: bool = True) -> str:
     return _LIB_PATH
 
 
+def _open(path):
+    """A built oracle library with its prototypes set (tests also open deliberately broken builds with it)."""
+    lib = ctypes.CDLL(path)
+    i64, ci, dbl, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+    lib.sga_forward.restype = ci
+    lib.sga_forward.argtypes = [i64, i64, vp, vp, ci, ci, dbl, vp, vp, vp, vp, vp, vp]
+    lib.sga_backward.restype = ci
+    lib.sga_backward.argtypes = [i64, i64, vp, vp, ci, ci, dbl, vp, vp, vp, vp, vp, vp, vp, ci]
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             build()
-        lib = ctypes.CDLL(_LIB_PATH)
-        i64, ci, dbl, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
-        lib.sga_forward.restype = ci
-        lib.sga_forward.argtypes = [i64, i64, vp, vp, ci, ci, dbl, vp, vp, vp, vp, vp, vp]
-        lib.sga_backward.restype = ci
-        lib.sga_backward.argtypes = [i64, i64, vp, vp, ci, ci, dbl, vp, vp, vp, vp, vp, vp, vp, ci]
-        _lib = lib
+        _lib = _open(_LIB_PATH)
     return _lib
 
 

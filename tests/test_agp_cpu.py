@@ -28,6 +28,9 @@ HAND = {
     "tie_prefers_fewer_gpus_listed_last": ((1.0, 1 << 20, [(1, 2, 2.0 ** -22), (0, 4, 1.5 * 2.0 ** -22)], 8), (1, 2, None)),
     # tie at the minimum at the same GPU count: the entry listed first
     "tie_same_gpus_first_listed": ((1.0, 1 << 20, [(1, 2, 2.0 ** -22), (0, 2, 2.0 ** -22), (2, 2, 2.0 ** -21)], 8), (1, 2, None)),
+    # the term, not the raw coefficient, is minimised: AG@2 has the smaller beta (3e-7 -> term 6e-7), A2A@8 the
+    # smaller term (8*3.2e-7/7 = 3.657e-7) -> GP-A2A on 8; estimate 1/8 + 3.2e-7*1e6 = 0.445 s
+    "term_not_raw_coefficient": ((1.0, 1_000_000, [(0, 2, 3e-7), (1, 8, 3.2e-7)], 8), (1, 8, 0.445)),
     # entries beyond the machine, or for one GPU, are ignored even when they have the smallest term
     "entries_outside_2_to_P_ignored": ((1.0, 1000, [(0, 16, 1e-9), (1, 1, 0.0), (0, 8, 5e-4)], 8), (0, 8, None)),
 }
@@ -90,3 +93,27 @@ def test_library_matches_reference_on_random_tables():
         c, s, _ = gta.gta_agp_select(t1, n, table, P)
         assert (c if c >= 0 else None, s) == (c_ref, s_ref), (trial, table)
     assert ties > 50 and boundaries > 50   # the dyadic tables did exercise both
+
+
+@pytest.mark.parametrize("old,new", [
+    ("i * b / (i - 1) <= k]", "i * b / (i - 1) < k]"),            # boundary excluded
+    ("if 2 <= i <= max_gpus and", "if 2 <= i and"),                # machine size ignored
+    ("(i * b / (i - 1), i, position, c)", "(i * b / (i - 1), -i, position, c)"),   # ties to MORE GPUs
+    ("(i * b / (i - 1), i, position, c)", "(i * b / (i - 1), i, -position, c)"),   # ties to the entry listed last
+    ("(i * b / (i - 1), i, position, c)", "(b, i, position, c)"),                  # raw coefficient instead of the term
+    ("k = t_iter1 / n_nodes", "k = t_iter1"),                                      # k not per node
+])
+def test_planted_mistakes_in_the_reference_are_caught_by_the_hand_worked_cases(old, new):
+    """The hand-worked cases alone (no library involved) notice each of these one-token mistakes."""
+    import inspect
+    text = inspect.getsource(agp_ref)
+    assert text.count(old) == 1
+    scope: dict = {}
+    exec(compile(text.replace(old, new), "agp_ref_mutant", "exec"), scope)
+    wrong = 0
+    for (t1, n, table, P), (c, s, _) in HAND.values():
+        got = scope["agp_select"](t1, n, as_beta(table), P)
+        if -got[1] == s:            # the mutant that negates the GPU count returns it negated
+            got = (got[0], -got[1])
+        wrong += got != (c, s)
+    assert wrong > 0
