@@ -282,6 +282,8 @@ def main() -> int:
     ap.add_argument("--layer", action="store_true",
                     help="also time one full layer (QKV / output projections on the matrix cores + attention), "
                          "forward and backward; bf16 workloads with n_src == n_dst only")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="record one step into a HIP graph and time its replays (small, launch-bound workloads)")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -336,12 +338,24 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    timed_step = step
+    if args.hip_graph:   # the calls only enqueue kernels, so a step can be recorded once and replayed
+        step()           # allocates the scratch buffers before the capture
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        timed_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
@@ -403,6 +417,7 @@ def main() -> int:
         "config": {"workload": w.name, "recipe": w.recipe, "n_dst": w.n_dst, "n_src": w.n_src, "nnz": w.nnz,
                    "heads": w.heads, "head_dim": w.head_dim, "accumulate": "f32",
                    "backward": "recompute-per-entry" if "bwd_dst" in kernels else "dZ-kept-per-entry",
+                   "launch": "hip-graph replay" if args.hip_graph else "eager",
                    "plan_ms": plan_ms, "wave_max_deg": int(plan.info().wave_max_deg),
                    "hub_chunk": int(plan.info().hub_chunk),
                    "plan_workspace_bytes": int(plan.workspace.numel()),
