@@ -250,6 +250,17 @@ size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d_out);
 gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in, int d_out,
                          gta_dtype dtype, void* scratch, size_t scratch_bytes, void* stream);
 
+/* p weight gradients of one shape (1 <= p <= 4), dW[k] = X[k]^T dY[k], each exactly what gta_linear_dw
+ * gives (same blocks, same summation order).  bfloat16: one launch; products that name the same X (the
+ * gradients of W_Q, W_K, W_V, W_o in Eq. 3 and 5 all multiply the layer input) run side by side on one
+ * XCD, so the X rows one of them fetches serve the others from that L2.  float: one product after the
+ * other.  X, dY, dW are HOST arrays of p device pointers; the dW[k] must be distinct.
+ * scratch (device): gta_linear_dw_group_scratch_bytes = p x gta_linear_dw_scratch_bytes.               */
+size_t gta_linear_dw_group_scratch_bytes(int64_t n, int d_in, int d_out, int p);
+gta_status gta_linear_dw_group(const void* const* X, const void* const* dY, float* const* dW, int p, int64_t n,
+                               int d_in, int d_out, gta_dtype dtype, void* scratch, size_t scratch_bytes,
+                               void* stream);
+
 /* Several projections that share operands, in one launch (bfloat16, d in {64, 128, 256}):
  *     Y[po][n, d] = sum_{pi < p_in} X[pi][n, d] * op(W[po * p_in + pi]) (+ C[po])      for po < p_out
  * with op as in gta_linear (trans_w = 0: W is [d, d] input x output; 1: output x input), fp32

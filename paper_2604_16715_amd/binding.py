@@ -110,6 +110,10 @@ def load_library():
     lib.gta_linear_dw_scratch_bytes.argtypes = [c_int64, c_int, c_int]
     lib.gta_linear_dw.restype = c_int
     lib.gta_linear_dw.argtypes = [vp, vp, vp, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
+    lib.gta_linear_dw_group_scratch_bytes.restype = c_size_t
+    lib.gta_linear_dw_group_scratch_bytes.argtypes = [c_int64, c_int, c_int, c_int]
+    lib.gta_linear_dw_group.restype = c_int
+    lib.gta_linear_dw_group.argtypes = [vp, vp, vp, c_int, c_int64, c_int, c_int, c_int, vp, c_size_t, vp]
     lib.gta_linear_group_scratch_bytes.restype = c_size_t
     lib.gta_linear_group_scratch_bytes.argtypes = [c_int, c_int, c_int]
     lib.gta_linear_group.restype = c_int
@@ -516,6 +520,35 @@ def gta_linear_dw(X, dY, dW=None):
     _check(lib.gta_linear_dw(_ptr(X), _ptr(dY), _ptr(dW), n, d_in, d_out, _dtype_code(X), _ptr(scratch),
                              scratch.numel(), _stream()))
     return dW
+
+
+def gta_linear_dw_group(Xs, dYs, dWs=None):
+    """dWs[k] [d_in, d_out] float32 = Xs[k].T @ dYs[k] for 1 to 4 products of one shape (one launch for bfloat16)."""
+    Xs, dYs = list(Xs), list(dYs)
+    p = len(Xs)
+    if not 1 <= p <= 4 or len(dYs) != p:
+        raise GtaError(1, "1 to 4 products, one dY per X")
+    n, d_in = _need2("X[0]", Xs[0])
+    d_out = _need2("dY[0]", dYs[0])[1]
+    dev, dt = Xs[0].device, Xs[0].dtype
+    if dWs is None:
+        dWs = [torch.empty((d_in, d_out), dtype=torch.float32, device=dev) for _ in range(p)]
+    dWs = list(dWs)
+    if len(dWs) != p:
+        raise GtaError(1, "one dW per product")
+    for k in range(p):
+        _need(f"X[{k}]", Xs[k], (n, d_in), dt, dev)
+        _need(f"dY[{k}]", dYs[k], (n, d_out), dt, dev)
+        _need(f"dW[{k}]", dWs[k], (d_in, d_out), torch.float32, dev)
+    if len({t.data_ptr() for t in dWs}) != p:
+        raise GtaError(1, "the dW tensors must be distinct")
+    lib = load_library()
+    arr = lambda ts: (c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+    nbytes = lib.gta_linear_dw_group_scratch_bytes(n, d_in, d_out, p)
+    scratch = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    _check(lib.gta_linear_dw_group(arr(Xs), arr(dYs), arr(dWs), p, n, d_in, d_out, _dtype_code(Xs[0]),
+                                   _ptr(scratch), scratch.numel(), _stream()))
+    return dWs
 
 
 def gta_linear_group(Xs, Ws, Cs=None, trans_w: bool = False, Ys=None):

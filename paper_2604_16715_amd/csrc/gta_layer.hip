@@ -30,7 +30,7 @@ LayerScratch layer_scratch(const gta_plan* plan, int heads, int head_dim, gta_dt
     const size_t attn = gta_attn_scratch_bytes(plan, heads, head_dim, dtype);
     if (attn == 0) return L;
     const int d = heads * head_dim;
-    const size_t dw = gta_linear_dw_scratch_bytes(plan->n_dst, d, d);
+    const size_t dw = gta_linear_dw_group_scratch_bytes(plan->n_dst, d, d, 4);
     L.shared = ((attn > dw ? attn : dw) + 255) & ~(size_t)255;
     L.pack = proj_group_supported(d, dtype) ? proj_group_scratch_bytes(d, 4) : 0;
     L.total = L.shared + L.pack;
@@ -96,10 +96,13 @@ extern "C" GTA_API gta_status gta_sga_layer_bwd(const gta_plan* plan, const int6
     if ((rc = gta_attn_bwd(plan, indptr, indices, Q, K, V, Y, lse, dXout, dQ, dK, dV, n, n, heads, head_dim, dtype,
                            scale, scratch, L.shared, stream)) != GTA_OK)
         return rc;
-    if ((rc = gta_linear_dw(X, dXout, dWo, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
-    if ((rc = gta_linear_dw(X, dQ, dWq, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
-    if ((rc = gta_linear_dw(X, dK, dWk, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
-    if ((rc = gta_linear_dw(X, dV, dWv, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
+    {
+        // the four weight gradients X^T dX', X^T dQ, X^T dK, X^T dV share X: one launch
+        const void* xs[4] = {X, X, X, X};
+        const void* dys[4] = {dXout, dQ, dK, dV};
+        float* dws[4] = {dWo, dWq, dWk, dWv};
+        if ((rc = gta_linear_dw_group(xs, dys, dws, 4, n, d, d, dtype, scratch, L.shared, stream)) != GTA_OK) return rc;
+    }
     if (L.pack > 0) {
         // dX = dX' W_o^T + dQ W_Q^T + dK W_K^T + dV W_V^T: one kernel, summed in fp32, rounded once
         const void* ins[4] = {dXout, dQ, dK, dV};

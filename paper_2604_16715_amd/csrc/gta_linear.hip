@@ -320,42 +320,62 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
 // 4 consecutive rows of the same 8 columns and writes one 8-byte word per column.  LDS rows are 18
 // dwords apart and consecutive lanes write consecutive row quads, which spreads both the 8-byte
 // writes and the 8-byte fragment reads over all banks.  The LDS block is double-buffered (one
-// workgroup barrier per 32 rows) and the global loads run Q blocks ahead in registers.
+// workgroup barrier per 32 rows; the next block is written while the current one is multiplied) and
+// the global loads run Q blocks ahead in registers.
 // Row blocks are reduced afterwards in a fixed order (k_reduce_partials): no atomics.
 constexpr int kDwKB = 32, kDwPitch = kDwKB + 4;   // rows per block; 36 bf16 = 18 dwords per LDS row
 
 template <int WI, int WO, int AI, int AO>
 constexpr size_t dw_lds_bytes() { return sizeof(uint16_t) * 2 * (size_t)(32 * WI * AI + 32 * WO * AO) * kDwPitch; }
 
-template <int WI, int WO, int AI, int AO, int Q>
+// A launch covers up to four products.  The workgroups of one row split that belong to different
+// products get consecutive places on the same XCD, so they run side by side: where two products name
+// the same X, the rows one of them brings into that XCD's L2 serve the other (KEEP_X: X is then read
+// with ordinary loads; an operand nobody else reads stays non-temporal).
+struct DwOperands { const uint16_t* X[4]; const uint16_t* dY[4]; };
+struct DwResults { float* dW[4]; };
+
+template <int WI, int WO, int AI, int AO, int Q, bool KEEP_X>
 __global__ void __launch_bounds__(64 * WI * WO, 8 / (WI * WO))   // 8 wavefronts per compute unit
-k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, float* __restrict__ partial,
+k_linear_dw(DwOperands ops, int products, float* __restrict__ partial,
             int64_t n, int d_in, int d_out, int64_t rows_per_split, int tiles_i, int tiles_o, int splits) {
     constexpr int T = 64 * WI * WO, TI = 32 * WI * AI, TO = 32 * WO * AO, KB = kDwKB, pitch = kDwPitch;
     static_assert(TI == T / 2 && TO == T / 2, "half of the threads stage X, the other half dY, one unit each");
     static_assert(Q % 2 == 0, "the buffer a queue slot goes to must not depend on the outer iteration");
+    static_assert(KB == 32, "a row block is two MFMA steps of 16 rows");
     extern __shared__ __align__(16) unsigned char dw_lds[];
     uint16_t* xs = reinterpret_cast<uint16_t*>(dw_lds);   // [2][TI][pitch]
     uint16_t* ys = xs + 2 * TI * pitch;                   // [2][TO][pitch]
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 5, r32 = lane & 31;
-    // the tiles of one row split get ids 8 apart (same XCD) so that the rows they share hit in one L2
+    const int lane = threadIdx.x & 63, g = lane >> 5, r32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index, in a scalar register
+    // the products and tiles of one row split get ids 8 apart (same XCD) so that the rows they share
+    // hit in one L2
     const int64_t bid = blockIdx.x, jj = bid >> 3;
     const int tiles = tiles_i * tiles_o;
-    const int tile = (int)(jj % tiles);
-    const int64_t split = (jj / tiles) * 8 + (bid & 7);
+    const int product = (int)(jj % products);
+    const int tile = (int)((jj / products) % tiles);
+    const int64_t split = (jj / products / tiles) * 8 + (bid & 7);
     if (split >= splits) return;   // whole workgroup leaves together
+    const uint16_t* X = product == 0 ? ops.X[0] : product == 1 ? ops.X[1] : product == 2 ? ops.X[2] : ops.X[3];
+    const uint16_t* dY = product == 0 ? ops.dY[0] : product == 1 ? ops.dY[1] : product == 2 ? ops.dY[2] : ops.dY[3];
     const int i0 = (tile % tiles_i) * TI, o0 = (tile / tiles_i) * TO;
-    const int64_t rbeg = split * rows_per_split;
+    const int64_t rbeg = split * rows_per_split;   // < n: the host rounds splits so that none is empty
     const int64_t rend = rbeg + rows_per_split < n ? rbeg + rows_per_split : n;
     const int wi = w / WO, wo = w % WO;
 
-    // loader role: the first T/2 threads stage X, the others dY; unit = 8 columns x 4 rows
-    const bool loads_x = threadIdx.x < T / 2;
+    // Loader role, per wavefront: the first half of the wavefronts stage X, the others dY; a thread's
+    // unit is 8 columns x 4 rows.  The operand's base and row length sit in scalar registers and the
+    // thread's place inside a row block is one 32-bit byte offset that never changes, so a load in
+    // the loop costs no vector arithmetic.  A unit past the last column (a ragged tile) reads
+    // column 0 instead: it only feeds gradient entries that are never stored.
+    const bool loads_x = w < WI * WO / 2;
     const int lt = threadIdx.x % (T / 2), rq = lt & 7, cu = lt >> 3;
     const uint16_t* src = loads_x ? X : dY;
     const int ld = loads_x ? d_in : d_out;
-    const int cbase = (loads_x ? i0 : o0) + cu * 8;
-    const bool col_ok = cbase < ld;
+    int cbase = (loads_x ? i0 : o0) + cu * 8;
+    if (cbase >= ld) cbase = 0;
+    const unsigned row_bytes = 2u * (unsigned)ld;
+    const unsigned voff = (unsigned)(rq * 4) * row_bytes + 2u * (unsigned)cbase;
     uint16_t* dst = (loads_x ? xs : ys) + (cu * 8) * pitch + rq * 4;
     constexpr int buf_stride = T / 2 * pitch;   // elements between the two buffers of an operand
 
@@ -367,63 +387,123 @@ k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, flo
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // register queue: the loads of row block s + Q are issued when block s is written to LDS
+    // register queue: a slot holds the unit of one row block; its loads are issued Q + 1 blocks ahead
     uint4 queue[Q][4];
-    auto fetch = [&](uint4 (&slot)[4], int64_t r0) {
+    auto load16 = [&](const char* p) {   // an operand read once is non-temporal (wavefront-uniform choice)
+        const u32x4* q = reinterpret_cast<const u32x4*>(p);
+        const u32x4 v = KEEP_X && loads_x ? *q : __builtin_nontemporal_load(q);
+        return make_uint4(v.x, v.y, v.z, v.w);
+    };
+    auto fetch_whole = [&](uint4 (&slot)[4], int64_t r0) {   // a block that lies inside the split: no checks
+        const char* base = reinterpret_cast<const char*>(src + r0 * ld);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int64_t r = r0 + rq * 4 + q;
-            slot[q] = make_uint4(0, 0, 0, 0);
-            if (col_ok && r < rend) {   // both operands are read once: non-temporal
-                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + r * ld + cbase));
-                slot[q] = make_uint4(v.x, v.y, v.z, v.w);
+        for (int q = 0; q < 4; ++q) slot[q] = load16(base + (size_t)q * row_bytes + voff);
+    };
+    auto fetch = [&](uint4 (&slot)[4], int64_t r0) {         // any block: rows past the end count as zero
+        if (r0 + KB <= rend) {
+            fetch_whole(slot, r0);
+        } else if (r0 < rend) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t r = r0 + rq * 4 + q;
+                const uint4 v = load16(reinterpret_cast<const char*>(src + (r < rend ? r : rbeg) * ld + cbase));
+                slot[q] = r < rend ? v : make_uint4(0, 0, 0, 0);
             }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) slot[q] = make_uint4(0, 0, 0, 0);
         }
     };
+    // unit of four rows of one operand -> LDS: each column of the unit becomes one 8-byte word (byte
+    // permutes pick the low or the high halves of two rows' dwords)
+    auto stage = [&](const uint4 (&slot)[4], int buf) {
+        uint16_t* my_dst = dst + buf * buf_stride;
+        const uint32_t* s0 = reinterpret_cast<const uint32_t*>(&slot[0]);
+        const uint32_t* s1 = reinterpret_cast<const uint32_t*>(&slot[1]);
+        const uint32_t* s2 = reinterpret_cast<const uint32_t*>(&slot[2]);
+        const uint32_t* s3 = reinterpret_cast<const uint32_t*>(&slot[3]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            constexpr uint32_t LOW = 0x05040100u, HIGH = 0x07060302u;
+            *reinterpret_cast<uint2*>(my_dst + (2 * c) * pitch) =
+                make_uint2(__builtin_amdgcn_perm(s1[c], s0[c], LOW), __builtin_amdgcn_perm(s3[c], s2[c], LOW));
+            *reinterpret_cast<uint2*>(my_dst + (2 * c + 1) * pitch) =
+                make_uint2(__builtin_amdgcn_perm(s1[c], s0[c], HIGH), __builtin_amdgcn_perm(s3[c], s2[c], HIGH));
+        }
+    };
+    // MFMA operands of one 16-row step, two register sets (one is multiplied while the other is read)
+    uint4 fa[2][AI], fb[2][AO];
+    auto fragments = [&](int set, int buf, int ks) {   // rows are 8-byte aligned only: two 8-byte reads each
+        const uint16_t* xb = xs + buf * buf_stride + (32 * AI * wi + r32) * pitch + 8 * g + ks;
+        const uint16_t* yb = ys + buf * buf_stride + (32 * AO * wo + r32) * pitch + 8 * g + ks;
+#pragma unroll
+        for (int t = 0; t < AI; ++t) {
+            const uint2* pa = reinterpret_cast<const uint2*>(xb + 32 * t * pitch);
+            const uint2 a0 = pa[0], a1 = pa[1];
+            fa[set][t] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+        }
+#pragma unroll
+        for (int t = 0; t < AO; ++t) {
+            const uint2* pb = reinterpret_cast<const uint2*>(yb + 32 * t * pitch);
+            const uint2 b0 = pb[0], b1 = pb[1];
+            fb[set][t] = make_uint4(b0.x, b0.y, b1.x, b1.y);
+        }
+    };
+    auto multiply = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < AI; ++a)
+#pragma unroll
+            for (int b = 0; b < AO; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[set][a]), as_frag(fb[set][b]), acc[a][b], 0, 0, 0);
+    };
+
+    // Block b lives in LDS buffer b & 1 and came through queue slot b % Q (Q is even, so inside the
+    // unrolled loop both are functions of i alone).  A block is multiplied in two halves, and each
+    // half hides the memory work of the next one:
+    //   first half  (rows 0-15 of block b, operands read earlier)  | reads the operands of rows 16-31
+    //                                                              | and writes block b + 1 to the other buffer
+    //   barrier
+    //   second half (rows 16-31)                                   | reads the operands of rows 0-15 of
+    //                                                              | block b + 1, issues the loads of block b + 1 + Q
+    // The other buffer was last read for block b - 1, and those reads were complete when the wavefront
+    // reached the previous barrier; what is written before a barrier is read after it.  Blocks past
+    // the end of the split hold zeros.
 #pragma unroll
     for (int i = 0; i < Q; ++i) fetch(queue[i], rbeg + (int64_t)i * KB);
-    for (int64_t rb = rbeg; rb < rend; rb += (int64_t)Q * KB) {
+    stage(queue[0], 0);
+    fetch(queue[0], rbeg + (int64_t)Q * KB);
+    __syncthreads();
+    fragments(0, 0, 0);
+    // The main loop runs while every block it fetches is a whole one and has no branch inside, so the
+    // wait for a queue slot leaves the newer slots' loads in flight; the last blocks take the checked form.
+    int64_t rb = rbeg;
+    for (; rb + (int64_t)(2 * Q + 1) * KB <= rend; rb += (int64_t)Q * KB) {
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            fragments(1, i & 1, 16);
+            stage(queue[(i + 1) % Q], (i + 1) & 1);
+            multiply(0);
+            __syncthreads();
+            fragments(0, (i + 1) & 1, 0);
+            fetch_whole(queue[(i + 1) % Q], rb + (int64_t)(i + Q + 1) * KB);
+            multiply(1);
+        }
+    }
+    for (; rb < rend; rb += (int64_t)Q * KB) {
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
             const int64_t r0 = rb + (int64_t)i * KB;
             if (r0 >= rend) break;   // uniform over the workgroup
-            // Buffer i & 1 was last read two blocks ago; every wavefront has passed the barrier of the
-            // block in between, which it reaches only after those reads.
-            uint16_t* my_dst = dst + (i & 1) * buf_stride;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {   // column e of the unit: its four rows become one 8-byte word
-                const uint32_t lo = half_of(queue[i][0], e) | (half_of(queue[i][1], e) << 16);
-                const uint32_t hi = half_of(queue[i][2], e) | (half_of(queue[i][3], e) << 16);
-                *reinterpret_cast<uint2*>(my_dst + e * pitch) = make_uint2(lo, hi);
-            }
+            fragments(1, i & 1, 16);
+            stage(queue[(i + 1) % Q], (i + 1) & 1);
+            multiply(0);
             __syncthreads();
-            fetch(queue[i], r0 + (int64_t)Q * KB);
-            const uint16_t* xb = xs + (i & 1) * buf_stride + (32 * AI * wi + r32) * pitch + 8 * g;
-            const uint16_t* yb = ys + (i & 1) * buf_stride + (32 * AO * wo + r32) * pitch + 8 * g;
-#pragma unroll
-            for (int ks = 0; ks < KB; ks += 16) {
-                uint4 af[AI], bf[AO];
-#pragma unroll
-                for (int t = 0; t < AI; ++t) {   // rows are 8-byte aligned only: two 8-byte reads per fragment
-                    const uint2* pa = reinterpret_cast<const uint2*>(xb + 32 * t * pitch + ks);
-                    const uint2 a0 = pa[0], a1 = pa[1];
-                    af[t] = make_uint4(a0.x, a0.y, a1.x, a1.y);
-                }
-#pragma unroll
-                for (int t = 0; t < AO; ++t) {
-                    const uint2* pb = reinterpret_cast<const uint2*>(yb + 32 * t * pitch + ks);
-                    const uint2 b0 = pb[0], b1 = pb[1];
-                    bf[t] = make_uint4(b0.x, b0.y, b1.x, b1.y);
-                }
-#pragma unroll
-                for (int a = 0; a < AI; ++a)
-#pragma unroll
-                    for (int b = 0; b < AO; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(af[a]), as_frag(bf[b]), acc[a][b], 0, 0, 0);
-            }
+            fragments(0, (i + 1) & 1, 0);
+            fetch(queue[(i + 1) % Q], r0 + (int64_t)(Q + 1) * KB);
+            multiply(1);
         }
     }
-    float* out = partial + split * d_in * d_out;
+    float* out = partial + ((int64_t)product * splits + split) * d_in * d_out;
 #pragma unroll
     for (int a = 0; a < AI; ++a)
 #pragma unroll
@@ -438,14 +518,16 @@ k_linear_dw(const uint16_t* __restrict__ X, const uint16_t* __restrict__ dY, flo
         }
 }
 
-// Sums the row splits' partial results in a fixed order: a workgroup takes 32 consecutive elements;
-// thread (element e, group j of 8) adds splits j, j + 8, ... and the 8 group sums are then added in
-// group order.
+// Sums the row splits' partial results in a fixed order: a workgroup takes 32 consecutive elements of
+// product blockIdx.y; thread (element e, group j of 8) adds splits j, j + 8, ... and the 8 group sums
+// are then added in group order.
 __global__ void __launch_bounds__(256)
-k_reduce_partials(const float* __restrict__ partial, float* __restrict__ dW, int64_t elems, int splits) {
+k_reduce_partials(const float* __restrict__ partials, DwResults res, int64_t elems, int splits) {
     __shared__ float part[8][32];
-    const int e = threadIdx.x & 31, j = threadIdx.x >> 5;
+    const int e = threadIdx.x & 31, j = threadIdx.x >> 5, product = blockIdx.y;
     const int64_t i = (int64_t)blockIdx.x * 32 + e;
+    const float* partial = partials + (int64_t)product * splits * elems;
+    float* dW = product == 0 ? res.dW[0] : product == 1 ? res.dW[1] : product == 2 ? res.dW[2] : res.dW[3];
     float acc = 0.f;
     if (i < elems)
         for (int s = j; s < splits; s += 8) acc += partial[(int64_t)s * elems + i];
@@ -559,46 +641,103 @@ extern "C" GTA_API size_t gta_linear_dw_scratch_bytes(int64_t n, int d_in, int d
     return sizeof(float) * (size_t)splits * (size_t)d_in * (size_t)d_out + 256;   // enough for either element type
 }
 
-extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in,
-                                            int d_out, gta_dtype dtype, void* scratch, size_t scratch_bytes,
-                                            void* stream) {
+extern "C" GTA_API size_t gta_linear_dw_group_scratch_bytes(int64_t n, int d_in, int d_out, int p) {
+    if (p < 1 || p > 4) return 0;
+    return (size_t)p * gta_linear_dw_scratch_bytes(n, d_in, d_out);
+}
+
+namespace gta {
+namespace {
+
+// p products dW[k] = X[k]^T dY[k] (1 <= p <= 4) of one shape.  bfloat16: one launch for all of them;
+// float: one after the other.
+gta_status linear_dw_products(const void* const* X, const void* const* dY, float* const* dW, int p, int64_t n,
+                              int d_in, int d_out, gta_dtype dtype, void* scratch, size_t scratch_bytes,
+                              hipStream_t st) {
     gta_status rc = check_dims(d_in, d_out, dtype);
     if (rc != GTA_OK) return rc;
+    if (p < 1 || p > 4) return fail(GTA_ERR_UNSUPPORTED, "1 to 4 products per call, got %d", p);
     if (n < 0) return fail(GTA_ERR_INVALID_ARG, "negative size");
-    if (!dW) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
-    if (n > 0 && (!X || !dY)) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
-    if (((uintptr_t)X & 15) || ((uintptr_t)dY & 15)) return fail(GTA_ERR_INVALID_ARG, "X and dY must be 16-byte aligned");
-    const size_t need = gta_linear_dw_scratch_bytes(n, d_in, d_out);
+    if (!X || !dY || !dW) return fail(GTA_ERR_INVALID_ARG, "null pointer array");
+    for (int k = 0; k < p; ++k) {
+        if (!dW[k]) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+        if (n > 0 && (!X[k] || !dY[k])) return fail(GTA_ERR_INVALID_ARG, "null tensor pointer");
+        if (((uintptr_t)X[k] & 15) || ((uintptr_t)dY[k] & 15))
+            return fail(GTA_ERR_INVALID_ARG, "X and dY must be 16-byte aligned");
+        for (int m = 0; m < k; ++m)
+            if (dW[m] == dW[k]) return fail(GTA_ERR_INVALID_ARG, "products %d and %d name the same result", m, k);
+    }
+    const size_t need = gta_linear_dw_group_scratch_bytes(n, d_in, d_out, p);
     if (!scratch || scratch_bytes < need) return fail(GTA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const DwGeometry g = dw_geometry(n, d_in, d_out, dtype);
     const int64_t elems = (int64_t)d_in * d_out;
     float* partial = static_cast<float*>(scratch);
-    {
-        LaunchTimer t("linear_dw", n, 0, st);
-        const int64_t blocks = (int64_t)(g.splits + 7) / 8 * 8 * g.tiles_i * g.tiles_o;
-        if (dtype == GTA_F32)
-            launch_linear_dw_f32((const float*)X, (const float*)dY, partial, n, d_in, d_out, g.rows_per_split,
-                                 g.tiles_i, g.tiles_o, g.splits, st);
-        else if (g.tile == 256) {   // 8 wavefronts, each 128 x 64 of the 256 x 256 tile
-            constexpr size_t lds = dw_lds_bytes<2, 4, 4, 2>();
-            GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear_dw<2, 4, 4, 2, 2>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL((k_linear_dw<2, 4, 4, 2, 2>), dim3((unsigned)blocks), dim3(512), lds, st,
-                               (const uint16_t*)X, (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split,
-                               g.tiles_i, g.tiles_o, g.splits);
-        } else {                    // 4 wavefronts, each 64 x 64 of the 128 x 128 tile
-            constexpr size_t lds = dw_lds_bytes<2, 2, 2, 2>();
-            hipLaunchKernelGGL((k_linear_dw<2, 2, 2, 2, 4>), dim3((unsigned)blocks), dim3(256), lds, st,
-                               (const uint16_t*)X, (const uint16_t*)dY, partial, n, d_in, d_out, g.rows_per_split,
-                               g.tiles_i, g.tiles_o, g.splits);
+    DwResults res{};
+    for (int k = 0; k < p; ++k) res.dW[k] = dW[k];
+    if (dtype == GTA_F32) {
+        for (int k = 0; k < p; ++k) {
+            {
+                LaunchTimer t("linear_dw", n, 0, st);
+                launch_linear_dw_f32((const float*)X[k], (const float*)dY[k], partial, n, d_in, d_out,
+                                     g.rows_per_split, g.tiles_i, g.tiles_o, g.splits, st);
+            }
+            LaunchTimer t("linear_dw.reduce", 0, 0, st);
+            DwResults one{};
+            one.dW[0] = dW[k];
+            hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, st, partial,
+                               one, elems, g.splits);
         }
+        GTA_HIP_TRY(hipGetLastError());
+        return GTA_OK;
+    }
+    DwOperands ops{};
+    bool shared_x = false;
+    for (int k = 0; k < p; ++k) {
+        ops.X[k] = (const uint16_t*)X[k];
+        ops.dY[k] = (const uint16_t*)dY[k];
+        for (int m = 0; m < k; ++m) shared_x = shared_x || X[m] == X[k];
+    }
+    {
+        LaunchTimer t(p == 1 ? "linear_dw" : "linear_dw_group", n, 0, st);
+        const int64_t blocks = (int64_t)(g.splits + 7) / 8 * 8 * g.tiles_i * g.tiles_o * p;
+#define GTA_LAUNCH_DW(WI, WO, AI, AO, Q, KEEP)                                                                     \
+    do {                                                                                                           \
+        constexpr size_t lds = dw_lds_bytes<WI, WO, AI, AO>();                                                     \
+        GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear_dw<WI, WO, AI, AO, Q, KEEP>,                         \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                    \
+        hipLaunchKernelGGL((k_linear_dw<WI, WO, AI, AO, Q, KEEP>), dim3((unsigned)blocks), dim3(64 * WI * WO),     \
+                           lds, st, ops, p, partial, n, d_in, d_out, g.rows_per_split, g.tiles_i, g.tiles_o,       \
+                           g.splits);                                                                              \
+    } while (0)
+        if (g.tile == 256) {   // 8 wavefronts, each 128 x 64 of the 256 x 256 tile
+            if (shared_x) GTA_LAUNCH_DW(2, 4, 4, 2, 2, true); else GTA_LAUNCH_DW(2, 4, 4, 2, 2, false);
+        } else {               // 4 wavefronts, each 64 x 64 of the 128 x 128 tile
+            if (shared_x) GTA_LAUNCH_DW(2, 2, 2, 2, 4, true); else GTA_LAUNCH_DW(2, 2, 2, 2, 4, false);
+        }
+#undef GTA_LAUNCH_DW
     }
     {
         LaunchTimer t("linear_dw.reduce", 0, 0, st);
-        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, st, partial, dW,
-                           elems, g.splits);
+        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((elems + 31) / 32), (unsigned)p), dim3(256), 0, st,
+                           partial, res, elems, g.splits);
     }
     GTA_HIP_TRY(hipGetLastError());
     return GTA_OK;
+}
+
+}  // namespace
+}  // namespace gta
+
+extern "C" GTA_API gta_status gta_linear_dw(const void* X, const void* dY, float* dW, int64_t n, int d_in,
+                                            int d_out, gta_dtype dtype, void* scratch, size_t scratch_bytes,
+                                            void* stream) {
+    return linear_dw_products(&X, &dY, &dW, 1, n, d_in, d_out, dtype, scratch, scratch_bytes,
+                              static_cast<hipStream_t>(stream));
+}
+
+extern "C" GTA_API gta_status gta_linear_dw_group(const void* const* X, const void* const* dY, float* const* dW,
+                                                  int p, int64_t n, int d_in, int d_out, gta_dtype dtype,
+                                                  void* scratch, size_t scratch_bytes, void* stream) {
+    return linear_dw_products(X, dY, dW, p, n, d_in, d_out, dtype, scratch, scratch_bytes,
+                              static_cast<hipStream_t>(stream));
 }

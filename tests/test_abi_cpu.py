@@ -93,5 +93,12 @@ def test_newer_entry_points_reject_bad_arguments_on_the_host(lib):
     assert rc == 2
     rc = lib.gta_linear_group(None, 1, None, 1, None, None, 10, 256, 1, 0, None, 0, None)      # null arrays
     assert rc == 1
+    # grouped weight gradients: the product count and the pointer arrays
+    assert lib.gta_linear_dw_group_scratch_bytes(1000, 64, 64, 3) == 3 * lib.gta_linear_dw_scratch_bytes(1000, 64, 64)
+    assert lib.gta_linear_dw_group_scratch_bytes(1000, 64, 64, 5) == 0
+    rc = lib.gta_linear_dw_group(None, None, None, 5, 10, 64, 64, 1, None, 0, None)
+    assert rc == 2 and b"products" in lib.gta_last_error()
+    rc = lib.gta_linear_dw_group(None, None, None, 2, 10, 64, 64, 1, None, 0, None)
+    assert rc == 1
     rc = lib.gta_stream_probe(3, None, None, None, 0, None)
     assert rc == 1 and b"mode" in lib.gta_last_error()

@@ -156,6 +156,46 @@ def test_linear_group(n, d):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("n,d_in,d_out,p", [(40001, 256, 256, 4), (1000, 128, 128, 3), (333, 64, 192, 2), (70000, 256, 128, 4),
+                                            (31, 16, 8, 4), (0, 64, 64, 2)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_linear_weight_gradient_group(n, d_in, d_out, p, dtype):
+    """Several weight gradients in one call (the four of Eq. 3 and 5 share the layer input): each equals,
+    bit for bit, the single-product entry point's result, which the tests above hold to the oracle."""
+    import paper_2604_16715_amd as gta
+    print(f"linear_dw_group case n={n} d_in={d_in} d_out={d_out} p={p} {dtype}", flush=True)
+    make = bf16_matrix if dtype == "bf16" else f32_matrix
+    f = (lambda a: gen.bf16_bits_to_f32(a).astype(np.float64)) if dtype == "bf16" else (lambda a: a.astype(np.float64))
+    X, X2 = make(n, d_in, 8, 2), make(n, d_in, 8, 3)
+    dYs = [make(n, d_out, 8, 10 + k) for k in range(p)]
+    Xd, X2d, dYd = to_torch(X), to_torch(X2), [to_torch(a) for a in dYs]
+    shared = gta.gta_linear_dw_group([Xd] * p, dYd)                       # every product reads the same X
+    mixed = gta.gta_linear_dw_group([Xd] * (p - 1) + [X2d], dYd)          # the last one its own
+    for k in range(p):
+        one = gta.gta_linear_dw(Xd, dYd[k])
+        assert torch.equal(shared[k], one), f"product {k}"
+        if n:
+            assert_close(f"X^T dY[{k}]", to_f64(one), dense_ref.linear_dw(f(X), f(dYs[k])), 1e-4 if dtype == "bf16" else F32_TOL)
+        else:
+            assert not one.any()
+    for k in range(p - 1):
+        assert torch.equal(mixed[k], shared[k])
+    assert torch.equal(mixed[p - 1], gta.gta_linear_dw(X2d, dYd[p - 1]))
+    torch.cuda.synchronize()
+
+
+def test_linear_weight_gradient_group_rejects():
+    import paper_2604_16715_amd as gta
+    X = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_dw_group([X] * 5, [X] * 5)          # at most four products
+    dW = torch.zeros((64, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_dw_group([X, X], [X, X], [dW, dW])  # results must be distinct
+    with pytest.raises(gta.GtaError):
+        gta.gta_linear_dw_group([X, X], [X])               # one dY per X
+
+
 def test_linear_group_rejects_unsupported():
     import paper_2604_16715_amd as gta
     X = torch.zeros((8, 96), dtype=torch.bfloat16, device="cuda")
