@@ -315,7 +315,8 @@ k_linear(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W, const u
 // TI x TO tile of dW (TI = 32 WI AI, TO = 32 WO AO) over one block of rows; wavefront (wi, wo) owns
 // AI x AO accumulator tiles of 32 x 32.  Two shapes are used: 128 x 128 with 4 wavefronts, and
 // 256 x 256 with 8 wavefronts when a dimension exceeds 128 — there a workgroup covers the whole
-// gradient at d = 256, so X and dY are each read exactly once.  Both operands have the reduction
+// gradient at d = 256, so X and dY are each read exactly once (a gradient that fits ONE such tile
+// takes k_linear_dw_direct further down instead; this kernel serves the other shapes).  Both operands have the reduction
 // index (the row) as their slow index, so each 32-row block is transposed into LDS: a thread loads
 // 4 consecutive rows of the same 8 columns and writes one 8-byte word per column.  LDS rows are 18
 // dwords apart and consecutive lanes write consecutive row quads, which spreads both the 8-byte
@@ -518,6 +519,190 @@ k_linear_dw(DwOperands ops, int products, float* __restrict__ partial,
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The 256 x 256 tile of X^T dY again, with the memory path of this chip: global memory goes straight
+// into LDS (global_load_lds, 16 bytes per lane, no registers in between), four row blocks are resident
+// so that three are in flight while one is multiplied, and the MFMA operands come out of LDS through
+// transposing reads (ds_read_b64_tr_b16), which turn the row-major blocks into "8 consecutive rows of
+// one column" per lane.  Nothing but matrix, LDS and load instructions is left in the loop, and the
+// accumulation order is that of k_linear_dw (same row splits, same 16-row steps): same bits.
+//
+// LDS image of one operand's 32-row x 256-column block (16 KB), in 16-byte units (one row, 8 columns):
+//   unit (k, c) with k the row and c = column / 8 sits at ((k / 4) * 8 + c / 4) * 16 + (k % 4) * 4 + c % 4,
+// i.e. 4 rows x 32 columns make one 256-byte group.  A load instruction fills 1 KB = 4 groups = 4 rows x
+// 128 columns: lane u fetches row 4 (k / 4) + (u % 16) / 4, unit 4 (group) + u % 4 (256 contiguous bytes
+// per row).  A transposing read returns to lane j of every 16 lanes element j % 4 of the 8-byte pieces
+// that lanes j / 4, j / 4 + 4, j / 4 + 8, j / 4 + 12 point at; with those four pointing at the same four
+// columns in rows k .. k + 3 the lane gets four consecutive rows of one column, and the 32 lanes of half
+// a wavefront touch exactly one 256-byte group: no bank conflicts.
+constexpr int kDdBufs = 4;
+constexpr int kDdPanelBytes = kDwKB * 256 * 2;                          // 16 KB
+constexpr size_t kDdLdsBytes = (size_t)kDdBufs * 2 * kDdPanelBytes;     // 128 KB
+__device__ __align__(16) unsigned int g_dd_zero_unit[4];                // what rows past the end read
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+#define GTA_LDS_PTR(T, p) reinterpret_cast<__attribute__((address_space(3))) T*>(reinterpret_cast<uintptr_t>(p))
+
+template <bool KEEP_X>
+__global__ void __launch_bounds__(512, 1)
+k_linear_dw_direct(DwOperands ops, int products, float* __restrict__ partial, int64_t n, int d_in, int d_out,
+                   int64_t rows_per_split, int splits) {
+    constexpr int KB = kDwKB, AI = 4, AO = 2, WO = 4;
+    extern __shared__ __align__(16) unsigned char dd_lds[];   // [buffer][X panel | dY panel]
+    const int lane = threadIdx.x & 63, g = lane >> 5, r32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t bid = blockIdx.x, jj = bid >> 3;
+    const int product = (int)(jj % products);
+    const int64_t split = (jj / products) * 8 + (bid & 7);
+    if (split >= splits) return;   // whole workgroup leaves together
+    const uint16_t* X = product == 0 ? ops.X[0] : product == 1 ? ops.X[1] : product == 2 ? ops.X[2] : ops.X[3];
+    const uint16_t* dY = product == 0 ? ops.dY[0] : product == 1 ? ops.dY[1] : product == 2 ? ops.dY[2] : ops.dY[3];
+    const int64_t rbeg = split * rows_per_split;   // < n: the host rounds splits so that none is empty
+    const int64_t rend = rbeg + rows_per_split < n ? rbeg + rows_per_split : n;
+    const int wi = w / WO, wo = w % WO;
+
+    // loader role: wavefronts 0-3 bring X, 4-7 dY; wavefront wq of an operand fills KB 4 wq .. 4 wq + 3 of
+    // the block's 16 (instruction q = 0..3: rows 8 wq + 4 (q / 2) .. + 3, columns 128 (q % 2) .. + 127)
+    const bool loads_x = w < 4;
+    const int wq = w & 3;
+    const uint16_t* src = loads_x ? X : dY;
+    const int ld = loads_x ? d_in : d_out;
+    const unsigned row_bytes = 2u * (unsigned)ld;
+    const int krow = lane % 16 / 4;                     // row of the lane inside the 4-row group
+    unsigned voff[2];                                    // byte offset of the lane's unit, for q % 2 = 0, 1
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        int c = 4 * (4 * h + lane / 16) + lane % 4;      // column unit
+        if (c * 8 >= ld) c = 0;                          // past the last column: feeds entries never stored
+        voff[h] = (unsigned)(8 * wq + krow) * row_bytes + 16u * (unsigned)c;
+    }
+    // The loads are written as assembly on purpose: the compiler then knows nothing of memory instructions
+    // that write LDS, and leaves their completion (vmcnt) to the waits placed by hand below; it would
+    // otherwise wait for ALL of them before any LDS read it cannot prove independent.  m0 holds the LDS
+    // byte address of the instruction's 1 KB; lane l's 16 bytes land at m0 + 16 l.
+    const bool keep = KEEP_X && loads_x;   // an operand read once is non-temporal (wavefront-uniform choice)
+    const unsigned my_panel = (unsigned)reinterpret_cast<uintptr_t>(GTA_LDS_PTR(unsigned char, dd_lds)) +
+                              (loads_x ? 0u : (unsigned)kDdPanelBytes) + (unsigned)wq * 4096u;
+    auto issue_whole = [&](int buf, int64_t r0) {   // a block that lies inside the split: no checks
+        const char* base0 = reinterpret_cast<const char*>(src + r0 * ld);
+        const char* base1 = base0 + 4 * (size_t)row_bytes;
+        const unsigned dst = my_panel + (unsigned)buf * (2u * kDdPanelBytes);
+#define GTA_DD_ISSUE(CACHE)                                                                                 \
+        asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\t"                                                       \
+                     "global_load_lds_dwordx4 %0, %2" CACHE "\n\t"                                           \
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"                                               \
+                     "global_load_lds_dwordx4 %1, %2" CACHE "\n\t"                                           \
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"                                               \
+                     "global_load_lds_dwordx4 %0, %3" CACHE "\n\t"                                           \
+                     "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"                                               \
+                     "global_load_lds_dwordx4 %1, %3" CACHE                                                  \
+                     : : "v"(voff[0]), "v"(voff[1]), "s"(base0), "s"(base1), "s"(dst) : "memory", "scc", "m0")
+        if (keep) GTA_DD_ISSUE(""); else GTA_DD_ISSUE(" nt");
+#undef GTA_DD_ISSUE
+    };
+    auto issue = [&](int buf, int64_t r0) {         // the last block: rows past the end read zeros
+        const unsigned dst = my_panel + (unsigned)buf * (2u * kDdPanelBytes);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t r = r0 + 8 * wq + 4 * (q / 2) + krow;
+            const char* p = reinterpret_cast<const char*>(src + r0 * ld) + (size_t)(q / 2) * 4 * row_bytes + voff[q % 2];
+            if (r >= rend) p = reinterpret_cast<const char*>(g_dd_zero_unit);
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                         : : "v"(p), "s"(dst + (unsigned)q * 1024u) : "memory", "m0");
+        }
+    };
+
+    // operand fragments: lane l supplies the address of row (l % 16) / 4 of its 16-lane group's four rows
+    // and of the 8-byte piece l % 4 of the group's 16 columns; the rows of a group are 8 g + 4 r .. + 3
+    const unsigned lane_off = (unsigned)(g * 4096 + ((lane % 16 / 4) * 4 + 2 * (lane / 16 % 2) + lane % 4 / 2) * 16 + (lane & 1) * 8);
+    const unsigned char* xfrag = dd_lds + lane_off + (AI * wi) * 256;
+    const unsigned char* yfrag = dd_lds + kDdPanelBytes + lane_off + (AO * wo) * 256;
+    uint4 fa[2][AI], fb[2][AO];
+    auto tr8 = [&](const unsigned char* p) {   // 8 consecutive rows of the lane's column: two transposing reads
+        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(GTA_LDS_PTR(short4v, p));
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(GTA_LDS_PTR(short4v, p + 2048));
+        const uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
+        return make_uint4(a.x, a.y, b.x, b.y);
+    };
+    auto fragments = [&](int set, int buf, int ks) {
+        const int o = buf * (2 * kDdPanelBytes) + (ks / 4) * 2048;
+#pragma unroll
+        for (int t = 0; t < AI; ++t) fa[set][t] = tr8(xfrag + o + t * 256);
+#pragma unroll
+        for (int t = 0; t < AO; ++t) fb[set][t] = tr8(yfrag + o + t * 256);
+    };
+    floatx16 acc[AI][AO];
+#pragma unroll
+    for (int a = 0; a < AI; ++a)
+#pragma unroll
+        for (int b = 0; b < AO; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    auto multiply = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < AI; ++a)
+#pragma unroll
+            for (int b = 0; b < AO; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[set][a]), as_frag(fb[set][b]), acc[a][b], 0, 0, 0);
+    };
+
+    // Block b lives in buffer b % 4.  While block b is multiplied, blocks b + 1 .. b + 3 are on their way
+    // (b + 3 is requested first thing; its buffer held block b - 1, whose last reads were complete at the
+    // previous barrier).  A wavefront's loads complete in order, so "at most 8 outstanding" means that its
+    // part of block b + 1 has landed; the barrier then makes every wavefront's part visible.  The first
+    // half of a block is multiplied while the second half's operands are read, the second half while the
+    // first operands of the next block are read.
+    const int64_t nwhole = (rend - rbeg) / KB, nblocks = (rend - rbeg + KB - 1) / KB;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        if (j < nwhole) issue_whole(j, rbeg + (int64_t)j * KB);
+        else if (j < nblocks) issue(j, rbeg + (int64_t)j * KB);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    fragments(0, 0, 0);
+    int64_t b = 0;
+    for (; b + 6 < nwhole; b += 4) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            issue_whole((i + 3) % 4, rbeg + (b + i + 3) * KB);
+            fragments(1, i, 16);
+            multiply(0);
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            __syncthreads();
+            fragments(0, (i + 1) % 4, 0);
+            multiply(1);
+        }
+    }
+    for (; b < nblocks; b += 4) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (b + i >= nblocks) break;   // uniform over the workgroup
+            if (b + i + 3 < nwhole) issue_whole((i + 3) % 4, rbeg + (b + i + 3) * KB);
+            else if (b + i + 3 < nblocks) issue((i + 3) % 4, rbeg + (b + i + 3) * KB);
+            fragments(1, i, 16);
+            multiply(0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            fragments(0, (i + 1) % 4, 0);   // past the last block: stale data, never multiplied
+            multiply(1);
+        }
+    }
+    float* out = partial + ((int64_t)product * splits + split) * d_in * d_out;
+#pragma unroll
+    for (int a = 0; a < AI; ++a)
+#pragma unroll
+        for (int bb = 0; bb < AO; ++bb) {
+            const int o = 32 * AO * wo + 32 * bb + r32;
+            if (o >= d_out) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 32 * AI * wi + 32 * a + out_row(v, lane);
+                if (i < d_in) out[(int64_t)i * d_out + o] = acc[a][bb][v];
+            }
+        }
+}
+
 // Sums the row splits' partial results in a fixed order: a workgroup takes 32 consecutive elements of
 // product blockIdx.y; thread (element e, group j of 8) adds splits j, j + 8, ... and the 8 group sums
 // are then added in group order.
@@ -709,7 +894,18 @@ gta_status linear_dw_products(const void* const* X, const void* const* dY, float
                            lds, st, ops, p, partial, n, d_in, d_out, g.rows_per_split, g.tiles_i, g.tiles_o,       \
                            g.splits);                                                                              \
     } while (0)
-        if (g.tile == 256) {   // 8 wavefronts, each 128 x 64 of the 256 x 256 tile
+        if (g.tile == 256 && g.tiles_i == 1 && g.tiles_o == 1) {   // one 256 x 256 tile: the LDS-direct form
+            GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear_dw_direct<true>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDdLdsBytes));
+            GTA_HIP_TRY(hipFuncSetAttribute((const void*)k_linear_dw_direct<false>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDdLdsBytes));
+            if (shared_x)
+                hipLaunchKernelGGL(k_linear_dw_direct<true>, dim3((unsigned)blocks), dim3(512), kDdLdsBytes, st, ops, p,
+                                   partial, n, d_in, d_out, g.rows_per_split, g.splits);
+            else
+                hipLaunchKernelGGL(k_linear_dw_direct<false>, dim3((unsigned)blocks), dim3(512), kDdLdsBytes, st, ops, p,
+                                   partial, n, d_in, d_out, g.rows_per_split, g.splits);
+        } else if (g.tile == 256) {   // 8 wavefronts, each 128 x 64 of a 256 x 256 tile
             if (shared_x) GTA_LAUNCH_DW(2, 4, 4, 2, 2, true); else GTA_LAUNCH_DW(2, 4, 4, 2, 2, false);
         } else {               // 4 wavefronts, each 64 x 64 of the 128 x 128 tile
             if (shared_x) GTA_LAUNCH_DW(2, 2, 2, 2, 4, true); else GTA_LAUNCH_DW(2, 2, 2, 2, 4, false);

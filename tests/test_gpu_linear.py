@@ -40,6 +40,7 @@ def test_linear_forward_forms(n, d_in, d_out):
 
 @pytest.mark.parametrize("n,d_in,d_out", [
     (1000, 128, 128), (70000, 256, 256), (333, 64, 192), (31, 16, 8), (4096, 512, 128), (5000, 48, 200),
+    (97, 256, 256), (129, 144, 256), (200000, 256, 176), (7, 256, 8),
 ])
 def test_linear_weight_gradient(n, d_in, d_out):
     import paper_2604_16715_amd as gta
@@ -157,7 +158,8 @@ def test_linear_group(n, d):
 
 
 @pytest.mark.parametrize("n,d_in,d_out,p", [(40001, 256, 256, 4), (1000, 128, 128, 3), (333, 64, 192, 2), (70000, 256, 128, 4),
-                                            (31, 16, 8, 4), (0, 64, 64, 2)])
+                                            (31, 16, 8, 4), (0, 64, 64, 2), (100, 256, 256, 3), (33, 208, 256, 2), (1, 256, 256, 1),
+                                            (300001, 256, 256, 2), (0, 256, 256, 2)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_linear_weight_gradient_group(n, d_in, d_out, p, dtype):
     """Several weight gradients in one call (the four of Eq. 3 and 5 share the layer input): each equals,
