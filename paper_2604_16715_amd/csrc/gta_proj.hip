@@ -53,8 +53,15 @@ __device__ __forceinline__ void wave_fence() {
 }
 
 // ---------------------------------------------------------------- weight repacking
-// Wp[(m * KCH + kc) * D + col][kk] = W_m(k = 32 kc + kk, col), where W_m(k, col) is W_m[k * D + col]
-// (trans = 0: stored [d_in, d_out]) or W_m[col * D + k] (trans = 1: stored [d_out, d_in]).
+// A chunk is the D x 32 slice W_m(k = 32 kc .. 32 kc + 31, all columns), W_m(k, col) being W_m[k * D + col]
+// (trans = 0: stored [d_in, d_out]) or W_m[col * D + k] (trans = 1: stored [d_out, d_in]).  Chunks follow each
+// other in the order (m, kc); inside a chunk the 16-byte unit u (8 consecutive k of one column) holds
+//     column 16 (u / 64) + u % 16,   k = 32 kc + 8 ((u / 16) % 4) .. + 7,
+// so 16 consecutive units are the same k piece of 16 consecutive columns.  A fetching wavefront reads
+// consecutive units and writes each to its column's LDS row: 16 lanes then write 16 different rows, which at
+// the row pitch of 20 dwords fall on different banks (4 lanes per 80-byte row, the plain order, would not).
+__device__ __forceinline__ int proj_unit_col(int u) { return 16 * (u >> 6) + (u & 15); }
+__device__ __forceinline__ int proj_unit_piece(int u) { return (u >> 4) & 3; }
 struct PackArgs { const uint16_t* W[kProjMaxParts * kProjMaxParts]; };
 __global__ void __launch_bounds__(256) k_pack_weights(PackArgs a, uint16_t* __restrict__ Wp, int D, int mats, int trans) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -62,8 +69,8 @@ __global__ void __launch_bounds__(256) k_pack_weights(PackArgs a, uint16_t* __re
     if (e >= per * mats) return;
     const int m = (int)(e / per);
     const int r = (int)(e - m * per);
-    const int kk = r % kProjKC, col = (r / kProjKC) % D, kc = r / (kProjKC * D);
-    const int k = kc * kProjKC + kk;
+    const int kc = r / (kProjKC * D), in_chunk = r % (kProjKC * D), u = in_chunk / 8;
+    const int col = proj_unit_col(u), k = kc * kProjKC + 8 * proj_unit_piece(u) + in_chunk % 8;
     const uint16_t* W = a.W[m];
     Wp[e] = trans ? W[(int64_t)col * D + k] : W[(int64_t)k * D + col];
 }
@@ -294,8 +301,8 @@ k_proj(ProjArgs a) {
                 uint16_t* dst = ws + buf * (D * WPitch);
 #pragma unroll
                 for (int i = 0; i < WU; ++i) {
-                    const unsigned u = lt + i * kFetchers;
-                    *reinterpret_cast<u32x4*>(dst + (u >> 2) * WPitch + (u & 3) * 8) = regs[set][i];
+                    const int u = (int)lt + i * kFetchers;
+                    *reinterpret_cast<u32x4*>(dst + proj_unit_col(u) * WPitch + proj_unit_piece(u) * 8) = regs[set][i];
                 }
             }
             __device__ __forceinline__ void prologue(int64_t) {
