@@ -231,7 +231,8 @@ def time_layer(gta, torch, plan, w, steps, log) -> dict:
     flops = 2.0 * n * d * d     # one n x d x d product
     tensor = n * d * el         # bytes of one [n, d] tensor
     # (products, tensors moved) per launch: every operand read once, every result written once
-    dense = {"linear_nn": (1, 2), "linear_nt": (1, 2), "linear_dw": (1, 2),
+    # (linear_dw_group: the four weight gradients of the layer share X: X once and four dY)
+    dense = {"linear_nn": (1, 2), "linear_nt": (1, 2), "linear_dw": (1, 2), "linear_dw_group": (4, 5),
              "proj_1to3": (3, 4), "proj_1to1+C": (1, 3), "proj_1to1": (1, 2), "proj_4to1": (4, 5)}
     ops = {}
     dense_ms = 0.0
