@@ -96,12 +96,20 @@ template <int D> struct ProjShape {
         sizeof(uint16_t) * ((size_t)kProjRows * XPitch + 2 * (size_t)D * kProjWPitch + 8 * 32 * (size_t)PPitch);
 };
 
+// register sets of a weight-fetching wavefront = weight chunks in flight: four at d = 256 (an L2 round trip
+// under load is longer than two chunks' worth of matrix instructions), two for the narrower shapes, whose
+// other wavefronts need the registers
+constexpr int proj_depth(int kch, bool small_form) { return kch % 8 == 0 && !small_form ? 4 : 2; }
+
 // The walk over (row block, output, input, weight chunk) that every wavefront of a workgroup makes, with
 // the workgroup barriers in it; what a wavefront does between the barriers depends on its role (hooks).
-template <int P_IN, int P_OUT, int KCH, class Hooks>
+template <int P_IN, int P_OUT, int KCH, int DEPTH, class Hooks>
 __device__ __forceinline__ void proj_walk(int64_t row_blocks, Hooks& h) {
     constexpr int TOTAL_CHUNKS = P_OUT * P_IN * KCH;
-    static_assert(KCH % 2 == 0, "chunks per product");   // chunk parity = LDS buffer, kept static by the pair below
+    // Chunk c is multiplied out of LDS buffer c % 2 and travels through register set c % DEPTH of the weight
+    // fetchers; both stay compile-time constants because the chunk loop is unrolled DEPTH at a time and a
+    // product's chunk count is a multiple of DEPTH.
+    static_assert(KCH % DEPTH == 0 && DEPTH % 2 == 0, "chunks per product");
     auto wrap = [](int ci) { return ci % TOTAL_CHUNKS; };   // (TOTAL_CHUNKS can be as small as 2)
     int64_t rb = blockIdx.x;
     if (rb >= row_blocks) return;   // whole workgroup leaves together
@@ -121,12 +129,13 @@ __device__ __forceinline__ void proj_walk(int64_t row_blocks, Hooks& h) {
                 const bool swap_x = P_IN > 1 || po == P_OUT - 1;
                 h.begin_product(rb, last_of_block ? next_rb : rb, po, pi, (pi + 1) % P_IN, swap_x);
 #pragma unroll 1
-                for (int kc = 0; kc < KCH; kc += 2) {
-                    h.chunk(kc, 0, wrap(ci + 3));
-                    __syncthreads();
-                    h.chunk(kc + 1, 1, wrap(ci + 4));
-                    __syncthreads();
-                    ci = wrap(ci + 2);
+                for (int kc = 0; kc < KCH; kc += DEPTH) {
+#pragma unroll
+                    for (int j = 0; j < DEPTH; ++j) {
+                        h.chunk(kc + j, j & 1, (j + 1) % DEPTH, wrap(ci + j + 1 + DEPTH));
+                        __syncthreads();
+                    }
+                    ci = wrap(ci + DEPTH);
                 }
                 h.end_product(rb, po, pi, swap_x);   // every wavefront has passed the last chunk's barrier: the X tile is free
                 if (swap_x) __syncthreads();
@@ -152,6 +161,7 @@ k_proj(ProjArgs a) {
     using S = ProjShape<D>;
     constexpr int CT = S::CT, RT = S::RT, XPitch = S::XPitch, PPitch = S::PPitch, KCH = S::KCH;
     constexpr int WPitch = kProjWPitch;
+    constexpr int DEPTH = proj_depth(KCH, SMALL);                 // weight chunks in flight
     constexpr int kFetchers = 128;                               // threads of each fetching role
     constexpr int XUnitsPerRow = D / 8, XU = kProjRows * XUnitsPerRow / kFetchers;   // X tile units per fetching thread
     constexpr int WUnits = D * (kProjKC / 8);                    // 16-byte units of a weight chunk
@@ -210,7 +220,7 @@ k_proj(ProjArgs a) {
                         }
                 }
             }
-            __device__ __forceinline__ void chunk(int kc, int buf, int) {   // one weight chunk: two k steps of 16
+            __device__ __forceinline__ void chunk(int kc, int buf, int, int) {   // one weight chunk: two k steps of 16
                 const uint16_t* wb = ws + buf * (D * WPitch) + (col0 + r32) * WPitch + 8 * g;
                 const uint16_t* xb = xs + (wr * RT * 32 + r32) * XPitch + kc * kProjKC + 8 * g;
                 constexpr int KS = kProjKC / 16;
@@ -281,17 +291,18 @@ k_proj(ProjArgs a) {
                 }
             }
         } h{a, xs, ws, patch, g, r32, wr, crow, cunit, col0, {}, {}};
-        proj_walk<P_IN, P_OUT, KCH>(a.row_blocks, h);
+        proj_walk<P_IN, P_OUT, KCH, DEPTH>(a.row_blocks, h);
     } else if (w < kProjConsumers + 2) {
         // ---------------------------------------------------------------- weight fetchers
-        // While chunk c is multiplied out of LDS buffer c % 2: chunk c + 1 (fetched two chunks ago) goes from its
-        // register set into the other buffer, which was last read before the previous barrier, and chunk c + 3 is
-        // fetched into the set that just became free, so an L2 round trip has two chunks to complete in.
+        // While chunk c is multiplied out of LDS buffer c % 2: chunk c + 1 (fetched DEPTH chunks ago) goes from its
+        // register set into the other buffer, which was last read before the previous barrier, and chunk
+        // c + 1 + DEPTH is fetched into the set that just became free, so an L2 round trip has DEPTH chunks to
+        // complete in.
         struct WeightFetcher {
             const ProjArgs& a;
             uint16_t* ws;
             unsigned lt;
-            u32x4 regs[2][WU];
+            u32x4 regs[DEPTH][WU];
             __device__ __forceinline__ void load(int set, int ci) {
                 const char* src = reinterpret_cast<const char*>(a.Wp + (int64_t)ci * (D * kProjKC));
 #pragma unroll
@@ -309,18 +320,19 @@ k_proj(ProjArgs a) {
                 constexpr int TOTAL = P_OUT * P_IN * KCH;
                 load(0, 0);
                 store(0, 0);
-                load(1, 1 % TOTAL);
-                load(0, 2 % TOTAL);
+#pragma unroll
+                for (int t = 1; t < DEPTH; ++t) load(t, t % TOTAL);
+                load(0, DEPTH % TOTAL);
             }
             __device__ __forceinline__ void begin_output() {}
             __device__ __forceinline__ void begin_product(int64_t, int64_t, int, int, int, bool) {}
-            __device__ __forceinline__ void chunk(int, int buf, int fetch_ci) {
-                store(buf ^ 1, buf ^ 1);
-                load(buf ^ 1, fetch_ci);
+            __device__ __forceinline__ void chunk(int, int buf, int next_set, int fetch_ci) {
+                store(next_set, buf ^ 1);
+                load(next_set, fetch_ci);
             }
             __device__ __forceinline__ void end_product(int64_t, int, int, bool) {}
         } h{a, ws, (unsigned)tid - 64u * kProjConsumers, {}};
-        proj_walk<P_IN, P_OUT, KCH>(a.row_blocks, h);
+        proj_walk<P_IN, P_OUT, KCH, DEPTH>(a.row_blocks, h);
     } else {
         // ---------------------------------------------------------------- X tile fetchers (one tile ahead)
         struct TileFetcher {
@@ -367,12 +379,12 @@ k_proj(ProjArgs a) {
             __device__ __forceinline__ void begin_product(int64_t, int64_t next_tile_rb, int, int, int next_pi, bool swap_x) {
                 if (swap_x) load(next_tile_rb, next_pi);
             }
-            __device__ __forceinline__ void chunk(int, int, int) {}
+            __device__ __forceinline__ void chunk(int, int, int, int) {}
             __device__ __forceinline__ void end_product(int64_t, int, int, bool swap_x) {
                 if (swap_x) store();
             }
         } h{a, xs, (unsigned)tid - 64u * (kProjConsumers + 2), {}};
-        proj_walk<P_IN, P_OUT, KCH>(a.row_blocks, h);
+        proj_walk<P_IN, P_OUT, KCH, DEPTH>(a.row_blocks, h);
     }
 }
 
