@@ -282,7 +282,8 @@ gta_status gta_linear_group(const void* const* X, int p_in, const void* const* W
  * dX [n, d], the weight gradients dW_* (float [d, d]) and uses dQ, dK, dV [n, d] as work buffers.
  * bfloat16 layers with d in {64, 128, 256} compute Q, K, V in one launch (X read once) and dX as one
  * four-term sum in fp32, rounded once (gta_linear_group); other shapes run one product per launch
- * and accumulate dX through the tensor type (rounded after each).  scratch:
+ * and accumulate dX through the tensor type (rounded after each).  The four weight gradients, which all
+ * multiply X, go through gta_linear_dw_group.  scratch:
  * gta_sga_layer_scratch_bytes.  Host-side sequencing of the entry points above.                  */
 size_t gta_sga_layer_scratch_bytes(const gta_plan* plan, int heads, int head_dim, gta_dtype dtype);
 gta_status gta_sga_layer_fwd(const gta_plan* plan, const int64_t* indptr, const int32_t* indices,
