@@ -68,3 +68,10 @@ def test_full_size_dense_projections():
     for k in range(4):   # bit-identical to the single-product entry point
         assert torch.equal(dWs[k], gta.gta_linear_dw(Xd[0], Xd[k]))
     torch.cuda.synchronize()
+
+
+def test_full_size_layer():
+    """One whole layer forward + backward (Eq. 3-5 and their gradients) on all of `large`, hidden 256, against
+    the float64 layer reference: Q, Y, X', dX and the four weight gradients, every element."""
+    import test_gpu_layer
+    test_gpu_layer.test_layer_forward_backward("large", 1, 8, 32)
